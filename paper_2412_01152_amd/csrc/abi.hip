@@ -1,0 +1,316 @@
+// Host side of the C ABI declared in include/diloco_mi355.h: argument checks, scratch layout,
+// and the launch sequence of each call.  Everything is enqueued on the caller's stream; nothing
+// here allocates, frees or waits for the device.
+#include <math.h>
+#include <string.h>
+
+#include "finalize_kernels.h"
+#include "kernels.h"
+#include "launch.h"
+#include "outer_kernel.h"
+
+using namespace diloco;
+
+namespace {
+
+// Segment offsets travel to the device inside kernel arguments (no staging copy, no host
+// synchronisation): 256 offsets per launch of a one-block kernel.
+struct OffsetBlock {
+    uint64_t v[256];
+};
+__global__ void upload_offsets_kernel(OffsetBlock blk, uint64_t* dst, uint32_t count) {
+    if (threadIdx.x < count) dst[threadIdx.x] = blk.v[threadIdx.x];
+}
+
+hipError_t upload_offsets(const uint64_t* host, uint32_t count, uint64_t* dst, hipStream_t stream) {
+    for (uint32_t first = 0; first < count; first += 256) {
+        OffsetBlock blk;
+        uint32_t c = count - first < 256 ? count - first : 256;
+        memcpy(blk.v, host + first, sizeof(uint64_t) * c);
+        hipLaunchKernelGGL(upload_offsets_kernel, dim3(1), dim3(256), 0, stream, blk, dst + first, c);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+int32_t check_segments(const uint64_t* seg, uint32_t T, uint64_t N) {
+    if (T == 0 || T > DILOCO_MAX_SEGMENTS) return DILOCO_ERR_SIZE;
+    if (!seg) return DILOCO_ERR_NULL;
+    if (seg[0] != 0 || seg[T] != N) return DILOCO_ERR_SIZE;
+    for (uint32_t s = 0; s < T; ++s)
+        if (seg[s + 1] < seg[s]) return DILOCO_ERR_SIZE;
+    return DILOCO_OK;
+}
+
+int32_t num_compute_units(int* out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int32_t)e;
+    e = hipDeviceGetAttribute(out, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return (int32_t)e;
+    if (*out < 1) *out = 1;
+    return 0;
+}
+
+// Uploads the offsets, clears the accumulators, and fills in the Pass record.
+int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, void* workspace,
+                   size_t workspace_bytes, hipStream_t stream) {
+    if (!workspace) return DILOCO_ERR_NULL;
+    if (misaligned(workspace, 256)) return DILOCO_ERR_ALIGN;
+    const WorkspaceLayout L = workspace_layout(T);
+    if (workspace_bytes < L.total) return DILOCO_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    p.N = N;
+    p.T = T;
+    p.seg = (const uint64_t*)(ws + L.seg);
+    p.stats = (double*)(ws + L.stats);
+    p.pivot = (float*)(ws + L.pivot);
+    p.hsum = (double*)(ws + L.hsum);
+    p.hcnt = (unsigned long long*)(ws + L.hcnt);
+    p.stream = stream;
+    int32_t rc = num_compute_units(&p.num_cus);
+    if (rc) return rc;
+    hipError_t e = upload_offsets(seg_host, T + 1, (uint64_t*)(ws + L.seg), stream);
+    if (e != hipSuccess) return (int32_t)e;
+    const size_t words = (L.total - L.stats) / sizeof(uint64_t);
+    const unsigned blocks = (unsigned)((words + 255) / 256 < 1024 ? (words + 255) / 256 : 1024);
+    hipLaunchKernelGGL(zero_kernel, dim3(blocks), dim3(256), 0, stream, (uint64_t*)(ws + L.stats), words);
+    e = hipGetLastError();
+    return e == hipSuccess ? 0 : (int32_t)e;
+}
+
+hipError_t finalize_qparams(const Pass& p, diloco_qparams* qp) {
+    hipLaunchKernelGGL(finalize_qparams_kernel, dim3((p.T + 255) / 256), dim3(256), 0, p.stream, p.seg, p.T,
+                       p.stats, p.pivot, qp);
+    return hipGetLastError();
+}
+
+hipError_t finalize_lut(const Pass& p, const diloco_qparams* qp, float* lut) {
+    hipLaunchKernelGGL(finalize_lut_kernel, dim3(p.T), dim3(kThreads), 0, p.stream, p.T, qp, p.hsum, p.hcnt,
+                       lut);
+    return hipGetLastError();
+}
+
+template <class Src>
+hipError_t run_stats(const Src& src, const Pass& p) {
+    hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + 255) / 256), dim3(256), 0, p.stream, src, p.seg, p.T,
+                       p.pivot);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr auto kernel = stats_kernel<Src, false>;
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
+                       g.per_block, p.stats, p.pivot, (float*)nullptr);
+    return hipGetLastError();
+}
+
+template <class Src>
+hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    constexpr auto kernel = quant_kernel<Src>;
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
+                       g.per_block, qp, codes, p.hsum, p.hcnt);
+    return hipGetLastError();
+}
+
+hipError_t reduce_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
+    switch (reduce_group_of(a.W)) {
+        case 0: return launch_reduce_stats_g0(a, p, acc_out);
+        case 1: return launch_reduce_stats_g1(a, p, acc_out);
+        case 2: return launch_reduce_stats_g2(a, p, acc_out);
+        default: return launch_reduce_stats_g3(a, p, acc_out);
+    }
+}
+
+hipError_t reduce_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    switch (reduce_group_of(a.W)) {
+        case 0: return launch_reduce_quant_g0(a, p, qp, codes);
+        case 1: return launch_reduce_quant_g1(a, p, qp, codes);
+        case 2: return launch_reduce_quant_g2(a, p, qp, codes);
+        default: return launch_reduce_quant_g3(a, p, qp, codes);
+    }
+}
+
+#define DILOCO_TRY(expr)                             \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return (int32_t)e_;    \
+    } while (0)
+
+template <int kOut>
+hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t* codes, const float* lut,
+                     const uint64_t* seg, uint32_t T, uint64_t N, float lr, float beta, void* local_out,
+                     int num_cus, hipStream_t stream) {
+    if (delta) {
+        constexpr auto kernel = outer_fp32_kernel<kOut>;
+        Grid g = plan_grid(N, num_cus, resident_blocks_per_cu<kernel>());
+        hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, delta, N,
+                           g.per_block, lr, beta, local_out);
+    } else {
+        constexpr auto kernel = outer_coded_kernel<kOut>;
+        Grid g = plan_grid(N, num_cus, resident_blocks_per_cu<kernel>());
+        hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, codes, lut, seg, T,
+                           N, g.per_block, lr, beta, local_out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t diloco_workspace_bytes(uint32_t T) {
+    if (T == 0 || T > DILOCO_MAX_SEGMENTS) return 0;
+    return workspace_layout(T).total;
+}
+
+const char* diloco_strerror(int32_t code) {
+    switch (code) {
+        case DILOCO_OK: return "ok";
+        case DILOCO_ERR_NULL: return "a required pointer is NULL";
+        case DILOCO_ERR_SIZE: return "bad size, segment table, W or divisor";
+        case DILOCO_ERR_ALIGN: return "a pointer is not aligned to its element type";
+        case DILOCO_ERR_WORKSPACE: return "workspace too small (see diloco_workspace_bytes)";
+        case DILOCO_ERR_DTYPE: return "unknown dtype flag";
+        default: break;
+    }
+    if (code > 0) return hipGetErrorString((hipError_t)code);
+    return "unknown error";
+}
+
+int32_t diloco_pseudograd_quantize(const float* theta_outer, const void* theta_local, int32_t local_dtype,
+                                   uint64_t N, const uint64_t* seg_offsets, uint32_t T, uint8_t* codes_out,
+                                   float* lut_out, diloco_qparams* qparams_out, void* workspace,
+                                   size_t workspace_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (local_dtype != DILOCO_DTYPE_FP32 && local_dtype != DILOCO_DTYPE_BF16) return DILOCO_ERR_DTYPE;
+    if (!lut_out || !qparams_out) return DILOCO_ERR_NULL;
+    if (N > 0 && (!theta_outer || !theta_local || !codes_out)) return DILOCO_ERR_NULL;
+    int32_t rc = check_segments(seg_offsets, T, N);
+    if (rc) return rc;
+    if (misaligned(theta_outer, 4) || misaligned(theta_local, local_dtype == DILOCO_DTYPE_BF16 ? 2 : 4) ||
+        misaligned(lut_out, 4) || misaligned(qparams_out, 8))
+        return DILOCO_ERR_ALIGN;
+    Pass p;
+    rc = begin_pass(p, N, T, seg_offsets, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    if (local_dtype == DILOCO_DTYPE_BF16) {
+        SrcPseudoGrad<true> src{theta_outer, theta_local};
+        if (N) DILOCO_TRY(run_stats(src, p));
+        DILOCO_TRY(finalize_qparams(p, qparams_out));
+        if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
+    } else {
+        SrcPseudoGrad<false> src{theta_outer, theta_local};
+        if (N) DILOCO_TRY(run_stats(src, p));
+        DILOCO_TRY(finalize_qparams(p, qparams_out));
+        if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
+    }
+    DILOCO_TRY(finalize_lut(p, qparams_out, lut_out));
+    return DILOCO_OK;
+}
+
+int32_t int8_reduce_chunk(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,
+                          const float* local_fp32, uint32_t divisor, uint64_t n, const uint64_t* seg_offsets,
+                          uint32_t T, float* acc_out, uint8_t* codes_out, float* lut_out,
+                          diloco_qparams* qparams_out, void* workspace, size_t workspace_bytes,
+                          void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (W > DILOCO_MAX_PEERS || (W == 0 && !local_fp32) || divisor == 0) return DILOCO_ERR_SIZE;
+    if (W > 0 && (!peer_codes || !peer_luts)) return DILOCO_ERR_NULL;
+    if (!lut_out || !qparams_out) return DILOCO_ERR_NULL;
+    if (n > 0 && !codes_out) return DILOCO_ERR_NULL;
+    int32_t rc = check_segments(seg_offsets, T, n);
+    if (rc) return rc;
+    ReduceArgs a;
+    memset(&a, 0, sizeof a);
+    a.W = W;
+    for (uint32_t p = 0; p < W; ++p) {
+        if (!peer_luts[p] || (n > 0 && !peer_codes[p])) return DILOCO_ERR_NULL;
+        if (misaligned(peer_luts[p], 4)) return DILOCO_ERR_ALIGN;
+        a.codes[p] = peer_codes[p];
+        a.luts[p] = peer_luts[p];
+    }
+    if (misaligned(local_fp32, 4) || misaligned(acc_out, 4) || misaligned(lut_out, 4) ||
+        misaligned(qparams_out, 8))
+        return DILOCO_ERR_ALIGN;
+    a.local = local_fp32;
+    if (divisor == 1) {
+        a.div_mode = kDivNone;
+        a.div = 1.0f;
+    } else if ((divisor & (divisor - 1)) == 0) {
+        a.div_mode = kDivPow2;       // multiplying by 2^-j rounds exactly like dividing by 2^j
+        a.div = 1.0f / (float)divisor;
+    } else {
+        a.div_mode = kDivTrue;
+        a.div = (float)divisor;
+    }
+    Pass p;
+    rc = begin_pass(p, n, T, seg_offsets, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    if (n) DILOCO_TRY(reduce_stats(a, p, acc_out));
+    DILOCO_TRY(finalize_qparams(p, qparams_out));
+    if (n) {
+        if (acc_out) {
+            SrcF32 src{acc_out};
+            DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
+        } else {
+            DILOCO_TRY(reduce_quant(a, p, qparams_out, codes_out));
+        }
+    }
+    DILOCO_TRY(finalize_lut(p, qparams_out, lut_out));
+    return DILOCO_OK;
+}
+
+int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* delta_fp32,
+                            const uint8_t* delta_codes, const float* delta_lut, const uint64_t* seg_offsets,
+                            uint32_t T, uint64_t N, float lr, float beta, void* theta_local_out,
+                            int32_t local_dtype, void* workspace, size_t workspace_bytes, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    const bool coded = delta_codes != nullptr || delta_lut != nullptr;
+    if (coded == (delta_fp32 != nullptr)) return DILOCO_ERR_NULL;       // exactly one form
+    if (coded && (!delta_codes || !delta_lut)) return DILOCO_ERR_NULL;
+    if (N > 0 && (!theta_outer || !momentum)) return DILOCO_ERR_NULL;
+    if (theta_local_out && local_dtype != DILOCO_DTYPE_FP32 && local_dtype != DILOCO_DTYPE_BF16)
+        return DILOCO_ERR_DTYPE;
+    if (misaligned(theta_outer, 4) || misaligned(momentum, 4) || misaligned(delta_fp32, 4) ||
+        misaligned(delta_lut, 4) ||
+        misaligned(theta_local_out, local_dtype == DILOCO_DTYPE_BF16 ? 2 : 4))
+        return DILOCO_ERR_ALIGN;
+    const uint64_t* seg_dev = nullptr;
+    if (coded) {
+        int32_t rc = check_segments(seg_offsets, T, N);
+        if (rc) return rc;
+        if (!workspace) return DILOCO_ERR_NULL;
+        if (misaligned(workspace, 256)) return DILOCO_ERR_ALIGN;
+        const WorkspaceLayout L = workspace_layout(T);
+        if (workspace_bytes < L.total) return DILOCO_ERR_WORKSPACE;
+        if (N == 0) return DILOCO_OK;
+        DILOCO_TRY(upload_offsets(seg_offsets, T + 1, (uint64_t*)((char*)workspace + L.seg), stream));
+        seg_dev = (const uint64_t*)((char*)workspace + L.seg);
+    }
+    if (N == 0) return DILOCO_OK;
+    int cus = 0;
+    int32_t rc = num_compute_units(&cus);
+    if (rc) return rc;
+    const int out = !theta_local_out ? kOutNone : (local_dtype == DILOCO_DTYPE_BF16 ? kOutBf16 : kOutF32);
+    switch (out) {
+        case kOutNone:
+            DILOCO_TRY(run_outer<kOutNone>(theta_outer, momentum, delta_fp32, delta_codes, delta_lut, seg_dev,
+                                           T, N, lr, beta, theta_local_out, cus, stream));
+            break;
+        case kOutF32:
+            DILOCO_TRY(run_outer<kOutF32>(theta_outer, momentum, delta_fp32, delta_codes, delta_lut, seg_dev,
+                                          T, N, lr, beta, theta_local_out, cus, stream));
+            break;
+        default:
+            DILOCO_TRY(run_outer<kOutBf16>(theta_outer, momentum, delta_fp32, delta_codes, delta_lut, seg_dev,
+                                           T, N, lr, beta, theta_local_out, cus, stream));
+            break;
+    }
+    return DILOCO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Device-side building blocks shared by the gfx950 kernels of this library: alignment-tolerant
+// vector access, the block's share of the flat buffer, segment lookup, wave64 / block reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/diloco_mi355.h"
+
+namespace diloco {
+
+constexpr int kThreads = 256;                       // 4 wave64 per block; also the number of buckets
+constexpr int kVec = 4;                             // consecutive elements per lane per load
+constexpr int kUnroll = 4;                          // loads in flight per stream per lane
+constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
+constexpr int kBuckets = 256;
+constexpr int kFlushIters = 8;                      // LDS fp32 bucket sums move to fp64 this often
+
+// Vector types that promise only element alignment: gfx950 global memory instructions accept
+// any byte address, so one dwordx4 / dwordx2 / dword access is emitted whatever the pointer's
+// alignment (chunk boundaries of a ring all-reduce are arbitrary element offsets).
+typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint16_t u16x4_u __attribute__((ext_vector_type(4), aligned(2)));
+typedef uint32_t u32_u __attribute__((aligned(1)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 ld_f32x4(const float* p) { return *(const f32x4_u*)p; }
+__device__ __forceinline__ void st_f32x4(float* p, f32x4 v) { *(f32x4_u*)p = v; }
+__device__ __forceinline__ uint32_t ld_u8x4(const uint8_t* p) { return *(const u32_u*)p; }
+__device__ __forceinline__ void st_u8x4(uint8_t* p, uint32_t v) { *(u32_u*)p = v; }
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ f32x4 ld_bf16x4(const uint16_t* p) {
+    u16x4_u h = *(const u16x4_u*)p;
+    f32x4 r;
+    r[0] = bf16_bits_to_f32(h[0]);
+    r[1] = bf16_bits_to_f32(h[1]);
+    r[2] = bf16_bits_to_f32(h[2]);
+    r[3] = bf16_bits_to_f32(h[3]);
+    return r;
+}
+
+// fp32 -> bf16 bit pattern, round to nearest even, NaN kept quiet.
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t b = __float_as_uint(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((b >> 16) | 0x40u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+
+// The flat buffer [0, N) is cut into equal contiguous shares, one per block; a share is a
+// multiple of kIter so that full iterations start on the same phase in every block.
+struct Share {
+    uint64_t begin, end;
+};
+__device__ __forceinline__ Share block_share(uint64_t N, uint64_t per_block) {
+    Share r;
+    r.begin = (uint64_t)blockIdx.x * per_block;
+    uint64_t e = r.begin + per_block;
+    r.end = e < N ? e : N;
+    return r;
+}
+
+// Index of the segment that holds element `pos` (pos < seg[T]): the smallest s with seg[s+1] > pos.
+__device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg, uint32_t T,
+                                                 uint64_t pos) {
+    uint32_t lo = 0, hi = T - 1;
+    while (lo < hi) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (seg[mid + 1] > pos)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Sum of two per-thread doubles over the block; result valid in thread 0.  `red` is 8 doubles of LDS.
+__device__ __forceinline__ void block_sum2(double& a, double& b, double* red) {
+    a = wave_sum(a);
+    b = wave_sum(b);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 0) {
+        red[wave] = a;
+        red[4 + wave] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = (red[0] + red[1]) + (red[2] + red[3]);
+        b = (red[4] + red[5]) + (red[6] + red[7]);
+    }
+}
+
+// Bucket index of Section 2.2's quantiser: floor((x - lo) / width) clipped to [0, 255], with the
+// subtraction and the multiplication by the reciprocal width as two separately rounded fp32
+// operations (never contracted into a fused multiply-add).  NaN goes to bucket 0.
+__device__ __forceinline__ int bucket_of(float x, float lo, float inv_w) {
+    float t = __fmul_rn(__fsub_rn(x, lo), inv_w);
+    int k = (int)t;
+    k = t >= 255.0f ? 255 : k;
+    k = !(t > 0.0f) ? 0 : k;
+    return k;
+}
+
+// fp32 bucket width and bucket centre used for the codebook sums: the kernel accumulates
+// (x - centre_k), whose magnitude is half a bucket, instead of x; the finalising kernel adds
+// centre_k back in fp64.  Both must use exactly these two functions.
+__device__ __forceinline__ float bucket_width(float inv_w) {
+    return inv_w > 0.0f ? __fdiv_rn(1.0f, inv_w) : 0.0f;
+}
+__device__ __forceinline__ float bucket_centre(int k, float lo, float w) {
+    return __fmaf_rn((float)k + 0.5f, w, lo);
+}
+
+// Device scratch layout (all offsets in bytes from a 256-byte aligned base).
+struct WorkspaceLayout {
+    size_t seg, stats, pivot, hsum, hcnt, total;
+};
+__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+__host__ inline WorkspaceLayout workspace_layout(uint32_t T) {
+    WorkspaceLayout L;
+    size_t o = 0;
+    L.seg = o;
+    o = align_up(o + sizeof(uint64_t) * ((size_t)T + 1), 256);
+    L.stats = o;
+    o = align_up(o + sizeof(double) * 2 * (size_t)T, 256);
+    L.pivot = o;
+    o = align_up(o + sizeof(float) * (size_t)T, 256);
+    L.hsum = o;
+    o = align_up(o + sizeof(double) * kBuckets * (size_t)T, 256);
+    L.hcnt = o;
+    o = align_up(o + sizeof(unsigned long long) * kBuckets * (size_t)T, 256);
+    L.total = o;
+    return L;
+}
+
+}  // namespace diloco

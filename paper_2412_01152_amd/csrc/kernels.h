@@ -1,0 +1,306 @@
+// Kernel templates of the quantising passes.
+//
+// Section 2.2's quantiser needs the statistics of a whole segment before any element can be coded,
+// so every quantising call is two streaming passes over its input:
+//   pass A  (stats_kernel)  values -> per-segment sum and sum of squares about a pivot, in fp64
+//   pass B  (quant_kernel)  values -> bucket index per element + per-bucket {count, sum}
+// with two tiny kernels between and after them that turn the sums into (lo, 1/width) and into the
+// codebook.  "Values" come from a source functor: the pseudo-gradient theta_outer - theta_local
+// (stage 1), the averaged fp32 sum of decoded peer contributions (stage 2), or a stored fp32 array.
+// Nothing but codes, codebooks and (when asked for) the fp32 accumulation is written.
+#pragma once
+
+#include "device_common.h"
+
+namespace diloco {
+
+// ------------------------------------------------------------------------------------------
+// sources
+// ------------------------------------------------------------------------------------------
+
+// Algorithm 1, outer-gradient line: d = theta_outer - theta_local, one fp32 subtraction.
+template <bool kLocalBf16>
+struct SrcPseudoGrad {
+    const float* theta_outer;
+    const void* theta_local;
+    static constexpr int kLdsFloats = 0;
+    struct Raw {
+        f32x4 a, b;
+    };
+    __device__ __forceinline__ void bind(float*) {}
+    __device__ __forceinline__ void enter_segment(uint32_t) {}
+    __device__ __forceinline__ Raw fetch4(uint64_t i) const {
+        Raw r;
+        r.a = ld_f32x4(theta_outer + i);
+        if (kLocalBf16)
+            r.b = ld_bf16x4((const uint16_t*)theta_local + i);
+        else
+            r.b = ld_f32x4((const float*)theta_local + i);
+        return r;
+    }
+    __device__ __forceinline__ f32x4 value4(const Raw& r) const {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __fsub_rn(r.a[e], r.b[e]);
+        return v;
+    }
+    __device__ __forceinline__ float value1(uint64_t i) const {
+        float b = kLocalBf16 ? bf16_bits_to_f32(((const uint16_t*)theta_local)[i])
+                             : ((const float*)theta_local)[i];
+        return __fsub_rn(theta_outer[i], b);
+    }
+    __device__ __forceinline__ float first_value(uint64_t i, uint32_t) const { return value1(i); }
+};
+
+// A stored fp32 array (second pass of stage 2 when the accumulation was written out).
+struct SrcF32 {
+    const float* x;
+    static constexpr int kLdsFloats = 0;
+    struct Raw {
+        f32x4 a;
+    };
+    __device__ __forceinline__ void bind(float*) {}
+    __device__ __forceinline__ void enter_segment(uint32_t) {}
+    __device__ __forceinline__ Raw fetch4(uint64_t i) const {
+        Raw r;
+        r.a = ld_f32x4(x + i);
+        return r;
+    }
+    __device__ __forceinline__ f32x4 value4(const Raw& r) const { return r.a; }
+    __device__ __forceinline__ float value1(uint64_t i) const { return x[i]; }
+    __device__ __forceinline__ float first_value(uint64_t i, uint32_t) const { return x[i]; }
+};
+
+// Section 2.2's reduction: decode each of the W coded contributions through its segment's
+// codebook (held in LDS), add them in contribution order in fp32 on top of the optional
+// un-quantised local value, then take the average of Algorithm 1 (division by k).
+enum DivMode { kDivNone = 0, kDivPow2 = 1, kDivTrue = 2 };
+
+template <int W, bool kHasLocal>
+struct SrcReduce {
+    static constexpr int kW = W > 0 ? W : 1;
+    const uint8_t* codes[kW];
+    const float* luts[kW];     // each [T][256]
+    const float* local;        // [n] or nullptr
+    float div;                 // divisor, or its exact reciprocal when it is a power of two
+    int div_mode;
+    float* lds;                // W tables of 256 floats
+    static constexpr int kLdsFloats = W * kBuckets;
+    struct Raw {
+        uint32_t c[kW];
+        f32x4 l;
+    };
+    __device__ __forceinline__ void bind(float* p) { lds = p; }
+    __device__ __forceinline__ void enter_segment(uint32_t s) {
+        if (W > 0) {
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < W; ++p)
+                lds[p * kBuckets + threadIdx.x] = luts[p][(size_t)s * kBuckets + threadIdx.x];
+            __syncthreads();
+        }
+    }
+    __device__ __forceinline__ float finish(float v) const {
+        if (div_mode == kDivPow2) return __fmul_rn(v, div);
+        if (div_mode == kDivTrue) return __fdiv_rn(v, div);
+        return v;
+    }
+    __device__ __forceinline__ Raw fetch4(uint64_t i) const {
+        Raw r;
+#pragma unroll
+        for (int p = 0; p < W; ++p) r.c[p] = ld_u8x4(codes[p] + i);
+        if (kHasLocal) r.l = ld_f32x4(local + i);
+        return r;
+    }
+    __device__ __forceinline__ f32x4 value4(const Raw& r) const {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float acc = kHasLocal ? r.l[e] : 0.0f;
+#pragma unroll
+            for (int p = 0; p < W; ++p)
+                acc = __fadd_rn(acc, lds[p * kBuckets + ((r.c[p] >> (8 * e)) & 0xffu)]);
+            v[e] = finish(acc);
+        }
+        return v;
+    }
+    __device__ __forceinline__ float value1(uint64_t i) const {
+        float acc = kHasLocal ? local[i] : 0.0f;
+#pragma unroll
+        for (int p = 0; p < W; ++p) acc = __fadd_rn(acc, lds[p * kBuckets + codes[p][i]]);
+        return finish(acc);
+    }
+    // Same value straight from global memory (no LDS tables needed): used for the pivot.
+    __device__ __forceinline__ float first_value(uint64_t i, uint32_t s) const {
+        float acc = kHasLocal ? local[i] : 0.0f;
+#pragma unroll
+        for (int p = 0; p < W; ++p)
+            acc = __fadd_rn(acc, luts[p][(size_t)s * kBuckets + codes[p][i]]);
+        return finish(acc);
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// pass A: statistics (Section 2.2 item 1)
+// ------------------------------------------------------------------------------------------
+// Each thread keeps fp64 sums of (x - c) and (x - c)^2 with c = first value of the segment: the
+// shift removes the cancellation of a large mean and makes a constant segment give exactly 0.
+// The pivots are written by a one-thread-per-segment kernel before the pass starts, because the
+// pass may overwrite its own input (accumulation stored in place over the local addend).
+// One pair of fp64 atomics per (block, segment).  When kWriteAcc, the values are also stored.
+template <class Src>
+__global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t T,
+                             float* __restrict__ pivot) {
+    uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= T) return;
+    pivot[s] = seg[s + 1] > seg[s] ? src.first_value(seg[s], s) : 0.0f;
+}
+
+template <class Src, bool kWriteAcc>
+__global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint64_t* __restrict__ seg,
+                                                        uint32_t T, uint64_t N, uint64_t per_block,
+                                                        double* __restrict__ stats,
+                                                        const float* __restrict__ pivot,
+                                                        float* acc_out) {
+    __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
+    __shared__ double s_red[8];
+    Src src = src_in;
+    src.bind(s_src);
+    const Share sh = block_share(N, per_block);
+    if (sh.begin >= sh.end) return;
+    const int tid = threadIdx.x;
+    uint32_t s = find_segment(seg, T, sh.begin);
+    uint64_t pos = sh.begin;
+    while (pos < sh.end) {
+        const uint64_t seg_end = seg[s + 1];
+        if (seg_end <= pos) {
+            ++s;
+            continue;
+        }
+        const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
+        src.enter_segment(s);
+        const double c64 = (double)pivot[s];
+        double s1 = 0.0, s2 = 0.0;
+        uint64_t base = pos;
+        for (; base + kIter <= sub_end; base += kIter) {
+            typename Src::Raw raw[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+                raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                f32x4 v = src.value4(raw[j]);
+                if (kWriteAcc) st_f32x4(acc_out + base + (uint64_t)(j * kThreads + tid) * kVec, v);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    double d = (double)v[e] - c64;
+                    s1 += d;
+                    s2 = fma(d, d, s2);
+                }
+            }
+        }
+        for (uint64_t i = base + tid; i < sub_end; i += kThreads) {
+            float v = src.value1(i);
+            if (kWriteAcc) acc_out[i] = v;
+            double d = (double)v - c64;
+            s1 += d;
+            s2 = fma(d, d, s2);
+        }
+        block_sum2(s1, s2, s_red);
+        if (tid == 0) {
+            atomicAdd(&stats[2 * (size_t)s], s1);
+            atomicAdd(&stats[2 * (size_t)s + 1], s2);
+        }
+        pos = sub_end;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// pass B: bucket index per element, and the per-bucket sums behind the codebook (item 4)
+// ------------------------------------------------------------------------------------------
+// One LDS histogram of {count, fp32 sum of (x - bucket centre)} per block, fed by LDS atomics.
+// Thread k owns bucket k: every kFlushIters iterations it moves the bucket's LDS partial into
+// fp64 registers (bounding the fp32 accumulation error), and when the block leaves the segment
+// it adds its totals to the segment's global bins with one fp64 and one integer atomic.
+template <class Src>
+__global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
+                                                        uint32_t T, uint64_t N, uint64_t per_block,
+                                                        const diloco_qparams* __restrict__ qp,
+                                                        uint8_t* __restrict__ codes,
+                                                        double* __restrict__ hsum,
+                                                        unsigned long long* __restrict__ hcnt) {
+    __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
+    __shared__ unsigned s_cnt[kBuckets];
+    __shared__ float s_sum[kBuckets];
+    Src src = src_in;
+    src.bind(s_src);
+    const Share sh = block_share(N, per_block);
+    if (sh.begin >= sh.end) return;
+    const int tid = threadIdx.x;
+    uint32_t s = find_segment(seg, T, sh.begin);
+    uint64_t pos = sh.begin;
+    while (pos < sh.end) {
+        const uint64_t seg_end = seg[s + 1];
+        if (seg_end <= pos) {
+            ++s;
+            continue;
+        }
+        const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
+        src.enter_segment(s);
+        const float lo = qp[s].lo;
+        const float inv_w = qp[s].inv_w;
+        const float w = bucket_width(inv_w);
+        double bin_sum = 0.0;
+        unsigned long long bin_cnt = 0;
+        s_cnt[tid] = 0;
+        s_sum[tid] = 0.0f;
+        __syncthreads();
+        uint64_t base = pos;
+        int since_flush = 0;
+        for (; base + kIter <= sub_end; base += kIter) {
+            typename Src::Raw raw[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+                raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                f32x4 v = src.value4(raw[j]);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int k = bucket_of(v[e], lo, inv_w);
+                    atomicAdd(&s_cnt[k], 1u);
+                    atomicAdd(&s_sum[k], __fsub_rn(v[e], bucket_centre(k, lo, w)));
+                    packed |= (uint32_t)k << (8 * e);
+                }
+                st_u8x4(codes + base + (uint64_t)(j * kThreads + tid) * kVec, packed);
+            }
+            if (++since_flush == kFlushIters) {
+                since_flush = 0;
+                __syncthreads();
+                bin_sum += (double)s_sum[tid];
+                bin_cnt += s_cnt[tid];
+                s_sum[tid] = 0.0f;
+                s_cnt[tid] = 0;
+                __syncthreads();
+            }
+        }
+        for (uint64_t i = base + tid; i < sub_end; i += kThreads) {
+            float v = src.value1(i);
+            int k = bucket_of(v, lo, inv_w);
+            atomicAdd(&s_cnt[k], 1u);
+            atomicAdd(&s_sum[k], __fsub_rn(v, bucket_centre(k, lo, w)));
+            codes[i] = (uint8_t)k;
+        }
+        __syncthreads();
+        bin_sum += (double)s_sum[tid];
+        bin_cnt += s_cnt[tid];
+        if (bin_cnt) {
+            atomicAdd(&hsum[(size_t)s * kBuckets + tid], bin_sum);
+            atomicAdd(&hcnt[(size_t)s * kBuckets + tid], bin_cnt);
+        }
+        pos = sub_end;
+    }
+}
+
+}  // namespace diloco

@@ -1,0 +1,79 @@
+// Host-side launch plumbing shared by the translation units of the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_common.h"
+
+namespace diloco {
+
+// Everything the two quantising passes share for one call.
+struct Pass {
+    uint64_t N;
+    uint32_t T;
+    const uint64_t* seg;        // device, [T+1]
+    double* stats;              // device, [T][2]
+    float* pivot;               // device, [T]
+    double* hsum;               // device, [T][256]
+    unsigned long long* hcnt;   // device, [T][256]
+    int num_cus;
+    hipStream_t stream;
+};
+
+struct ReduceArgs {
+    const uint8_t* codes[DILOCO_MAX_PEERS];
+    const float* luts[DILOCO_MAX_PEERS];
+    uint32_t W;
+    const float* local;
+    float div;
+    int div_mode;
+};
+
+// Resident blocks per compute unit of a kernel, looked up once per process.
+template <auto Kernel>
+inline int resident_blocks_per_cu() {
+    static int occ = 0;
+    if (occ == 0) {
+        int v = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, Kernel, kThreads, 0) != hipSuccess || v < 1)
+            v = 4;
+        occ = v;
+    }
+    return occ;
+}
+
+// One contiguous share of the flat buffer per block, all blocks resident at once: grid = CUs x
+// resident blocks (fewer when the buffer is small), share rounded up to whole iterations.
+struct Grid {
+    uint32_t blocks;
+    uint64_t per_block;
+};
+inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu) {
+    Grid g;
+    uint64_t want = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
+    uint64_t iters = (N + kIter - 1) / kIter;
+    if (iters < 1) iters = 1;
+    if (want > iters) want = iters;
+    uint64_t iters_per_block = (iters + want - 1) / want;
+    g.per_block = iters_per_block * kIter;
+    g.blocks = (uint32_t)((N + g.per_block - 1) / g.per_block);
+    if (g.blocks < 1) g.blocks = 1;
+    return g;
+}
+
+// Stage 2 launchers; the W values are spread over several translation units (groups of W) so they
+// compile in parallel.  Each returns hipErrorInvalidValue for a W outside its group.
+#define DILOCO_DECLARE_REDUCE_GROUP(G)                                                           \
+    hipError_t launch_reduce_stats_g##G(const ReduceArgs& a, const Pass& p, float* acc_out);    \
+    hipError_t launch_reduce_quant_g##G(const ReduceArgs& a, const Pass& p,                     \
+                                        const diloco_qparams* qp, uint8_t* codes);
+DILOCO_DECLARE_REDUCE_GROUP(0)
+DILOCO_DECLARE_REDUCE_GROUP(1)
+DILOCO_DECLARE_REDUCE_GROUP(2)
+DILOCO_DECLARE_REDUCE_GROUP(3)
+#undef DILOCO_DECLARE_REDUCE_GROUP
+
+inline int reduce_group_of(uint32_t W) { return W <= 4 ? 0 : (W <= 8 ? 1 : (W <= 12 ? 2 : 3)); }
+
+}  // namespace diloco

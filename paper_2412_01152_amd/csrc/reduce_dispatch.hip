@@ -1,0 +1,113 @@
+// Stage 2 kernels for one group of W values (number of coded contributions), selected at compile
+// time with -DDILOCO_W_GROUP=0..3 : W in {0..4}, {5..8}, {9..12}, {13..16}.  W is a template
+// argument so that all W code-stream loads of an iteration are in flight together and the W
+// codebooks sit at fixed LDS offsets.
+#include "kernels.h"
+#include "launch.h"
+
+#ifndef DILOCO_W_GROUP
+#error "compile with -DDILOCO_W_GROUP=0..3"
+#endif
+
+namespace diloco {
+namespace {
+
+template <int W, bool kLocal>
+SrcReduce<W, kLocal> make_src(const ReduceArgs& a) {
+    SrcReduce<W, kLocal> s;
+    for (int p = 0; p < SrcReduce<W, kLocal>::kW; ++p) {
+        s.codes[p] = p < W ? a.codes[p] : nullptr;
+        s.luts[p] = p < W ? a.luts[p] : nullptr;
+    }
+    s.local = a.local;
+    s.div = a.div;
+    s.div_mode = a.div_mode;
+    s.lds = nullptr;
+    return s;
+}
+
+template <int W, bool kLocal, bool kWriteAcc>
+hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
+    using Src = SrcReduce<W, kLocal>;
+    hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + 255) / 256), dim3(256), 0, p.stream,
+                       make_src<W, kLocal>(a), p.seg, p.T, p.pivot);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    constexpr auto kernel = stats_kernel<Src, kWriteAcc>;
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal>(a), p.seg,
+                       p.T, p.N, g.per_block, p.stats, p.pivot, acc_out);
+    return hipGetLastError();
+}
+
+template <int W, bool kLocal>
+hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    using Src = SrcReduce<W, kLocal>;
+    constexpr auto kernel = quant_kernel<Src>;
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal>(a), p.seg,
+                       p.T, p.N, g.per_block, qp, codes, p.hsum, p.hcnt);
+    return hipGetLastError();
+}
+
+template <int W>
+hipError_t stats_w(const ReduceArgs& a, const Pass& p, float* acc_out) {
+    if (a.local) {
+        return acc_out ? run_stats<W, true, true>(a, p, acc_out) : run_stats<W, true, false>(a, p, acc_out);
+    }
+    if constexpr (W == 0)
+        return hipErrorInvalidValue;
+    else
+        return acc_out ? run_stats<W, false, true>(a, p, acc_out)
+                       : run_stats<W, false, false>(a, p, acc_out);
+}
+
+template <int W>
+hipError_t quant_w(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    if (a.local) return run_quant<W, true>(a, p, qp, codes);
+    if constexpr (W == 0)
+        return hipErrorInvalidValue;
+    else
+        return run_quant<W, false>(a, p, qp, codes);
+}
+
+}  // namespace
+
+#define DILOCO_CAT2(a, b) a##b
+#define DILOCO_CAT(a, b) DILOCO_CAT2(a, b)
+#define DILOCO_STATS_FN DILOCO_CAT(launch_reduce_stats_g, DILOCO_W_GROUP)
+#define DILOCO_QUANT_FN DILOCO_CAT(launch_reduce_quant_g, DILOCO_W_GROUP)
+
+#if DILOCO_W_GROUP == 0
+#define DILOCO_W0 0
+#else
+#define DILOCO_W0 (DILOCO_W_GROUP * 4 + 1)
+#endif
+
+hipError_t DILOCO_STATS_FN(const ReduceArgs& a, const Pass& p, float* acc_out) {
+    switch ((int)a.W - DILOCO_W0) {
+        case 0: return stats_w<DILOCO_W0 + 0>(a, p, acc_out);
+        case 1: return stats_w<DILOCO_W0 + 1>(a, p, acc_out);
+        case 2: return stats_w<DILOCO_W0 + 2>(a, p, acc_out);
+        case 3: return stats_w<DILOCO_W0 + 3>(a, p, acc_out);
+#if DILOCO_W_GROUP == 0
+        case 4: return stats_w<4>(a, p, acc_out);
+#endif
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t DILOCO_QUANT_FN(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    switch ((int)a.W - DILOCO_W0) {
+        case 0: return quant_w<DILOCO_W0 + 0>(a, p, qp, codes);
+        case 1: return quant_w<DILOCO_W0 + 1>(a, p, qp, codes);
+        case 2: return quant_w<DILOCO_W0 + 2>(a, p, qp, codes);
+        case 3: return quant_w<DILOCO_W0 + 3>(a, p, qp, codes);
+#if DILOCO_W_GROUP == 0
+        case 4: return quant_w<4>(a, p, qp, codes);
+#endif
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace diloco

@@ -1,0 +1,338 @@
+"""GPU-vs-oracle parity, element by element, through the C ABI (needs an MI355X).
+
+Every test generates seeded synthetic inputs once, hands the same bits to the CPU oracle and to the
+library, and compares with the tolerances in parity_utils.  Stage-isolated tests feed each GPU
+stage the oracle's outputs of the previous stage, so a single edge flip upstream cannot cascade;
+the chained test runs GPU stage into GPU stage.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_01152_amd import synth
+from parity_utils import (bf16_bits, check_acc, check_codes, check_luts, check_outer, check_qparams,
+                          t2n)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2412_01152_amd import binding
+    binding.load()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return binding
+
+
+def _oracle_stage1(oracle_mod, theta, local, off):
+    if local.dtype == torch.bfloat16:
+        return oracle_mod.pseudograd_quantize(t2n(theta), bf16_bits(local), off, local_is_bf16=True)
+    return oracle_mod.pseudograd_quantize(t2n(theta), t2n(local), off)
+
+
+def _check_stage1(B, oracle_mod, theta, local, off, label):
+    say(f"[stage1] {label}: N={theta.numel()} T={len(off) - 1} dtype={local.dtype}")
+    codes, luts, qp = B.pseudograd_quantize(theta, local, off)
+    torch.cuda.synchronize()
+    o_codes, o_luts, o_qp, o_d = _oracle_stage1(oracle_mod, theta, local, off)
+    g_qp = B.qparams_to_numpy(qp)
+    exact = check_qparams(g_qp, o_qp)
+    flips = check_codes(t2n(codes), o_codes, o_d, off, o_qp)
+    worst = check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+    say(f"[stage1] {label}: flips={flips} exact-scale segments={exact}/{len(off) - 1} worst lut rel={worst:.2e}")
+    return codes, luts, qp
+
+
+# ---------------------------------------------------------------------------------------------
+# stage 1
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("local_dtype", [torch.float32, torch.bfloat16])
+def test_stage1_config0(B, oracle_mod, local_dtype):
+    theta, locals_, off = synth.make_inputs(synth.config_segment_sizes(0), 1, device=DEV,
+                                            local_dtype=local_dtype)
+    _check_stage1(B, oracle_mod, theta, locals_[0], off, "config0")
+
+
+@pytest.mark.parametrize("kind", ["mixture", "student_t3"])
+def test_stage1_ragged_segments(B, oracle_mod, kind):
+    sizes = synth.ragged_sizes(3_000_000)
+    theta, locals_, off = synth.make_inputs(sizes, 1, kind=kind, device=DEV)
+    _check_stage1(B, oracle_mod, theta, locals_[0], off, f"ragged/{kind}")
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_stage1_misaligned_pointers(B, oracle_mod, shift):
+    """Element-aligned only: fp32 pointers off by 4*shift bytes, codes off by `shift` bytes."""
+    sizes = [5000, 70_001, 12_345, 262_144 + 3]
+    n = sum(sizes)
+    theta_full, locals_, _ = synth.make_inputs([n + 8], 1, device=DEV)
+    theta = theta_full[shift:shift + n]
+    local = locals_[0][shift:shift + n]
+    off = synth.offsets_from_sizes(sizes)
+    codes_buf = torch.zeros(n + 16, dtype=torch.uint8, device=DEV)
+    codes_view = codes_buf[shift:shift + n]
+    codes, luts, qp = B.pseudograd_quantize(theta, local, off, codes_out=codes_view)
+    torch.cuda.synchronize()
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(
+        np.ascontiguousarray(t2n(theta)), np.ascontiguousarray(t2n(local)), off)
+    check_qparams(B.qparams_to_numpy(qp), o_qp)
+    check_codes(t2n(codes), o_codes, o_d, off, o_qp)
+    check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+    # nothing written outside the view
+    assert int(codes_buf[:shift].sum()) == 0 and int(codes_buf[shift + n:].sum()) == 0
+
+
+def test_stage1_bf16_misaligned(B, oracle_mod):
+    sizes = [4099, 100_000]
+    n = sum(sizes)
+    theta_full, locals_, _ = synth.make_inputs([n + 8], 1, device=DEV, local_dtype=torch.bfloat16)
+    theta, local = theta_full[3:3 + n], locals_[0][1:1 + n]      # different phases on purpose
+    off = synth.offsets_from_sizes(sizes)
+    codes, luts, qp = B.pseudograd_quantize(theta, local, off)
+    torch.cuda.synchronize()
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(
+        np.ascontiguousarray(t2n(theta)), bf16_bits(local.contiguous()), off, local_is_bf16=True)
+    check_qparams(B.qparams_to_numpy(qp), o_qp)
+    check_codes(t2n(codes), o_codes, o_d, off, o_qp)
+    check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+
+
+def test_stage1_zero_delta_joiner(B, oracle_mod):
+    """A node that joins without blocking contributes an all-zero pseudo-gradient (Section 2.4.2)."""
+    sizes = [4096, 100_001, 1]
+    theta, _, off = synth.make_inputs(sizes, 0, device=DEV)
+    local = theta.clone()
+    codes, luts, qp = B.pseudograd_quantize(theta, local, off)
+    torch.cuda.synchronize()
+    g_qp = B.qparams_to_numpy(qp)
+    assert np.all(g_qp["status"] == B.STATUS_DEGENERATE)
+    assert np.all(t2n(codes) == 0)
+    assert np.all(t2n(luts)[:, 0] == 0.0) and np.all(np.isfinite(t2n(luts)))
+    o_codes, o_luts, o_qp, _ = oracle_mod.pseudograd_quantize(t2n(theta), t2n(local), off)
+    check_qparams(g_qp, o_qp)
+    assert np.array_equal(t2n(luts), o_luts)
+
+
+def test_stage1_outlier_and_constant_segment(B, oracle_mod):
+    sizes = [50_000, 8192, 30_000]
+    theta, locals_, off = synth.make_inputs(sizes, 1, device=DEV)
+    local = locals_[0]
+    local[off[1]:off[2]] = theta[off[1]:off[2]] - 0.125            # constant pseudo-gradient 0.125
+    local[17] = theta[17] - 3.0                                     # one huge outlier
+    local[off[2] + 5] = theta[off[2] + 5] + 7.0
+    _check_stage1(B, oracle_mod, theta, local, off, "outlier+constant")
+
+
+def test_stage1_is_repeatable(B):
+    theta, locals_, off = synth.make_inputs(synth.ragged_sizes(1_000_000), 1, device=DEV)
+    c1, l1, _ = B.pseudograd_quantize(theta, locals_[0], off)
+    c2, l2, _ = B.pseudograd_quantize(theta, locals_[0], off)
+    torch.cuda.synchronize()
+    assert torch.equal(c1, c2)                                      # codes never depend on atomics' order
+    assert torch.allclose(l1, l2, rtol=1e-6, atol=0)
+
+
+def test_empty_input(B):
+    off = [0, 0]
+    theta = torch.empty(0, dtype=torch.float32, device=DEV)
+    codes, luts, qp = B.pseudograd_quantize(theta, theta.clone(), off)
+    torch.cuda.synchronize()
+    g = B.qparams_to_numpy(qp)
+    assert g["status"][0] == B.STATUS_EMPTY and np.all(t2n(luts) == 0)
+
+
+# ---------------------------------------------------------------------------------------------
+# stage 2 (fed with the oracle's stage-1 outputs)
+# ---------------------------------------------------------------------------------------------
+
+def _oracle_peers(oracle_mod, sizes, W, kind="mixture", seed=synth.BASE_SEED):
+    theta, locals_, off = synth.make_inputs(sizes, W, kind=kind, device="cpu", seed=seed)
+    st = [oracle_mod.pseudograd_quantize(theta.numpy(), l.numpy(), off) for l in locals_]
+    return theta, off, st
+
+
+def _run_stage2(B, oracle_mod, off, st, W, divisor, local=None, with_acc=False, alias=False):
+    peer_codes = [torch.from_numpy(s[0]).to(DEV) for s in st[:W]]
+    peer_luts = [torch.from_numpy(s[1]).to(DEV) for s in st[:W]]
+    n = off[-1]
+    local_t = torch.from_numpy(local).to(DEV) if local is not None else None
+    acc_t = None
+    if with_acc:
+        acc_t = local_t if (alias and local_t is not None) else torch.empty(n, dtype=torch.float32, device=DEV)
+    codes, luts, qp = B.reduce_chunk(peer_codes, peer_luts, off, divisor, local_fp32=local_t, acc_out=acc_t)
+    torch.cuda.synchronize()
+    o_acc, o_codes, o_luts, o_qp = oracle_mod.reduce([s[0] for s in st[:W]], [s[1] for s in st[:W]], off,
+                                                     divisor, local_fp32=local)
+    check_qparams(B.qparams_to_numpy(qp), o_qp)
+    flips = check_codes(t2n(codes), o_codes, o_acc, off, o_qp)
+    check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+    if with_acc:
+        mag = np.abs(local).astype(np.float64) if local is not None else np.zeros(n)
+        so = np.asarray(off)
+        for s_ in st[:W]:
+            for k in range(len(off) - 1):
+                mag[so[k]:so[k + 1]] += np.abs(s_[1][k][s_[0][so[k]:so[k + 1]]])
+        unequal = check_acc(t2n(acc_t), o_acc, np.maximum(np.abs(o_acc), mag / divisor))
+        assert unequal == 0, "fp32 accumulation is a fixed sequence of rounded operations: must be bit-equal"
+    return flips
+
+
+@pytest.mark.parametrize("W", list(range(1, 17)))
+def test_stage2_all_w(B, oracle_mod, W):
+    sizes = [100_000, 4096, 3, 77_777, 0, 40_001]
+    _, off, st = _oracle_peers(oracle_mod, sizes, W)
+    say(f"[stage2] W={W} recompute")
+    _run_stage2(B, oracle_mod, off, st, W, divisor=W)
+    say(f"[stage2] W={W} materialise")
+    _run_stage2(B, oracle_mod, off, st, W, divisor=W, with_acc=True)
+
+
+@pytest.mark.parametrize("W,divisor", [(0, 1), (0, 3), (1, 2), (4, 5), (13, 14), (16, 17)])
+@pytest.mark.parametrize("alias", [False, True])
+def test_stage2_local_addend(B, oracle_mod, W, divisor, alias):
+    sizes = [65_536, 12_289, 150_000]
+    theta, off, st = _oracle_peers(oracle_mod, sizes, max(W, 1))
+    local = oracle_mod.pseudograd(theta.numpy(), synth.fill_theta_local(
+        torch.empty_like(theta), theta, 99).numpy())
+    say(f"[stage2] W={W} +local divisor={divisor} alias={alias}")
+    _run_stage2(B, oracle_mod, off, st, W, divisor, local=local, with_acc=True, alias=alias)
+    if not alias:
+        _run_stage2(B, oracle_mod, off, st, W, divisor, local=local, with_acc=False)
+
+
+def test_stage2_divisor_one_and_retry_with_fewer_peers(B, oracle_mod):
+    sizes = [200_000]
+    _, off, st = _oracle_peers(oracle_mod, sizes, 6)
+    _run_stage2(B, oracle_mod, off, st, 6, divisor=1, with_acc=True)
+    _run_stage2(B, oracle_mod, off, st, 6, divisor=6)
+    _run_stage2(B, oracle_mod, off, st, 5, divisor=5)        # the retry: same buffers, one peer less
+
+
+def test_stage2_heavy_tails_w14(B, oracle_mod):
+    sizes = [300_000, 50_000]
+    _, off, st = _oracle_peers(oracle_mod, sizes, 14, kind="student_t3")
+    _run_stage2(B, oracle_mod, off, st, 14, divisor=14, with_acc=True)
+    _run_stage2(B, oracle_mod, off, st, 14, divisor=14)
+
+
+def test_stage2_misaligned_chunk(B, oracle_mod):
+    """A ring chunk that starts at an odd element offset: every stream has its own phase."""
+    sizes = [123_457]
+    n = sizes[0]
+    _, off, st = _oracle_peers(oracle_mod, sizes, 3)
+    bufs = [torch.zeros(n + 16, dtype=torch.uint8, device=DEV) for _ in range(3)]
+    peer_codes = []
+    for p in range(3):
+        v = bufs[p][p + 1:p + 1 + n]
+        v.copy_(torch.from_numpy(st[p][0]))
+        peer_codes.append(v)
+    peer_luts = [torch.from_numpy(s[1]).to(DEV) for s in st]
+    local_np = (np.random.default_rng(5).normal(0, 1e-3, n)).astype(np.float32)
+    local_buf = torch.zeros(n + 8, dtype=torch.float32, device=DEV)
+    local_v = local_buf[3:3 + n]
+    local_v.copy_(torch.from_numpy(local_np))
+    out_buf = torch.zeros(n + 16, dtype=torch.uint8, device=DEV)
+    codes, luts, qp = B.reduce_chunk(peer_codes, peer_luts, off, 4, local_fp32=local_v, acc_out=local_v,
+                                     codes_out=out_buf[5:5 + n])
+    torch.cuda.synchronize()
+    o_acc, o_codes, o_luts, o_qp = oracle_mod.reduce([s[0] for s in st], [s[1] for s in st], off, 4,
+                                                     local_fp32=local_np)
+    check_qparams(B.qparams_to_numpy(qp), o_qp)
+    check_codes(t2n(codes), o_codes, o_acc, off, o_qp)
+    check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+    assert np.array_equal(t2n(local_v), o_acc)
+    assert int(out_buf[:5].sum()) == 0 and int(out_buf[5 + n:].sum()) == 0
+    assert float(local_buf[:3].abs().sum()) == 0 and float(local_buf[3 + n:].abs().sum()) == 0
+
+
+# ---------------------------------------------------------------------------------------------
+# stage 3
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("coded", [False, True])
+@pytest.mark.parametrize("out", [None, torch.float32, torch.bfloat16])
+def test_stage3_outer_step(B, oracle_mod, coded, out):
+    sizes = [100_000, 4097, 1, 250_000]
+    n = sum(sizes)
+    off = synth.offsets_from_sizes(sizes)
+    rng = np.random.default_rng(11)
+    theta = rng.normal(0, 0.02, n).astype(np.float32)
+    mom = rng.normal(0, 2e-3, n).astype(np.float32)
+    g = (rng.normal(0, 1e-3, n)).astype(np.float32)
+    o_codes, o_luts, _ = oracle_mod.quantize_segments(g, off)
+    th_t, m_t = torch.from_numpy(theta).to(DEV), torch.from_numpy(mom).to(DEV)
+    out_t = torch.empty(n, dtype=out, device=DEV) if out is not None else None
+    th_o, m_o = theta.copy(), mom.copy()
+    lr, beta = 0.7, 0.9
+    for step in range(2):
+        old_th, old_m = th_o.copy(), m_o.copy()
+        if coded:
+            B.outer_step(th_t, m_t, lr, beta, delta_codes=torch.from_numpy(o_codes).to(DEV),
+                         delta_lut=torch.from_numpy(o_luts).to(DEV), seg_offsets=off, theta_local_out=out_t)
+            o_out = oracle_mod.outer_step(th_o, m_o, lr, beta, delta_codes=o_codes, delta_luts=o_luts,
+                                          seg_offsets=off,
+                                          local_out_dtype={None: None, torch.float32: "fp32",
+                                                           torch.bfloat16: "bf16"}[out])
+            gg = np.concatenate([o_luts[s][o_codes[off[s]:off[s + 1]]] for s in range(len(sizes))])
+        else:
+            B.outer_step(th_t, m_t, lr, beta, delta_fp32=torch.from_numpy(g).to(DEV), theta_local_out=out_t)
+            o_out = oracle_mod.outer_step(th_o, m_o, lr, beta, delta_fp32=g,
+                                          local_out_dtype={None: None, torch.float32: "fp32",
+                                                           torch.bfloat16: "bf16"}[out])
+            gg = g
+        torch.cuda.synchronize()
+        step_scale = lr * np.abs(gg.astype(np.float64) + beta * m_o)
+        check_outer(t2n(m_t), m_o, old_m, np.abs(gg), "momentum")
+        check_outer(t2n(th_t), th_o, old_th, step_scale, "theta")
+        if out is torch.float32:
+            assert torch.equal(out_t, th_t)
+        if out is torch.bfloat16:
+            assert torch.equal(out_t, th_t.to(torch.bfloat16))          # rounding of the GPU's own theta
+            ob = o_out.view(np.uint16).astype(np.int64)
+            gb = bf16_bits(out_t).astype(np.int64)
+            assert np.abs(gb - ob).max() <= 1                           # at most one bf16 step from the oracle's
+
+
+# ---------------------------------------------------------------------------------------------
+# chained: GPU stage into GPU stage, configuration 0 end to end
+# ---------------------------------------------------------------------------------------------
+
+def test_chained_config0(B, oracle_mod):
+    W = synth.config_peers(0)
+    theta, locals_, off = synth.make_inputs(synth.config_segment_sizes(0), W, device=DEV)
+    n = theta.numel()
+    g1 = [B.pseudograd_quantize(theta, l, off) for l in locals_]
+    codes2, luts2, qp2 = B.reduce_chunk([g[0] for g in g1], [g[1] for g in g1], off, W)
+    mom = torch.zeros(n, dtype=torch.float32, device=DEV)
+    theta_new = theta.clone()
+    B.outer_step(theta_new, mom, 0.7, 0.9, delta_codes=codes2, delta_lut=luts2, seg_offsets=off)
+    torch.cuda.synchronize()
+
+    th_np = t2n(theta)
+    o1 = [oracle_mod.pseudograd_quantize(th_np, t2n(l), off) for l in locals_]
+    for p in range(W):
+        check_qparams(B.qparams_to_numpy(g1[p][2]), o1[p][2])
+        check_codes(t2n(g1[p][0]), o1[p][0], o1[p][3], off, o1[p][2])
+    o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[0] for o in o1], [o[1] for o in o1], off, W)
+    check_qparams(B.qparams_to_numpy(qp2), o_q2)
+    flips = check_codes(t2n(codes2), o_c2, o_acc, off, o_q2, budget=1e-5)   # upstream flips may add a few
+    th_o, m_o = th_np.copy(), np.zeros(n, dtype=np.float32)
+    oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=off)
+    g_dec = o_l2[0][o_c2]
+    w2 = 12 * o_q2["std"][0] / 256
+    diff = np.abs(t2n(theta_new).astype(np.float64) - th_o)
+    same = t2n(codes2) == o_c2
+    scale = np.maximum(np.abs(th_o), 0.7 * 1.9 * np.abs(g_dec))
+    assert np.all(diff[same] <= 1e-5 * scale[same])
+    assert np.all(diff[~same] <= 0.7 * 1.9 * 1.01 * w2 + 1e-5 * scale[~same])   # a flipped code moves by one bucket
+    say(f"[chained] config0: stage-2 flips={flips}")
