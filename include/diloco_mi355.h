@@ -165,6 +165,21 @@ int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* de
                             float beta, void* theta_local_out, int32_t local_dtype,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Instrumentation for benchmarks (not part of the method).  After this call, every later call of
+ * the three operations made from the same host thread records HIP events on its stream around its
+ * streaming kernels, so a harness can time each kernel without a profiler:
+ *     events[0], events[1]   before / after the first streaming pass  (statistics pass of the two
+ *                            quantising calls; the only pass of outer_nesterov_step)
+ *     events[2], events[3]   before / after the second streaming pass (bucketise + codebook sums);
+ *                            not recorded by outer_nesterov_step
+ *   events   HOST array of 4 hipEvent_t created by the caller with timing enabled, or NULL to stop
+ *            recording.  The array is copied; the events stay owned by the caller and must outlive
+ *            the calls that record them.
+ * Returns DILOCO_OK.
+ */
+int32_t diloco_profile_passes(void* const* events);
+
 #ifdef __cplusplus
 }
 #endif

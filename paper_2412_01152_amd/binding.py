@@ -29,7 +29,7 @@ QPARAMS_BYTES = 40
 assert QPARAMS_DTYPE.itemsize == QPARAMS_BYTES
 
 EXPORTS = ("diloco_workspace_bytes", "diloco_strerror", "diloco_pseudograd_quantize",
-           "int8_reduce_chunk", "outer_nesterov_step")
+           "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes")
 
 _lib = None
 
@@ -61,8 +61,21 @@ def load() -> ctypes.CDLL:
     lib.int8_reduce_chunk.argtypes = [vp, vp, u32, vp, u32, u64, vp, u32, vp, vp, vp, vp, vp, sz, vp]
     lib.outer_nesterov_step.restype = i32
     lib.outer_nesterov_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u64, f32, f32, vp, i32, vp, sz, vp]
+    lib.diloco_profile_passes.restype = i32
+    lib.diloco_profile_passes.argtypes = [vp]
     _lib = lib
     return lib
+
+
+def profile_passes(events: Optional[Sequence[int]]) -> None:
+    """diloco_profile_passes: 4 raw hipEvent_t handles (ints), or None to stop recording."""
+    lib = load()
+    if events is None:
+        lib.diloco_profile_passes(ctypes.c_void_p(0))
+        return
+    assert len(events) == 4
+    arr = (ctypes.c_void_p * 4)(*events)
+    lib.diloco_profile_passes(ctypes.cast(arr, ctypes.c_void_p))
 
 
 def workspace_bytes(T: int) -> int:

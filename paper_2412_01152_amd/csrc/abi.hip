@@ -11,6 +11,13 @@
 
 using namespace diloco;
 
+namespace diloco {
+PassEvents& pass_events() {
+    static thread_local PassEvents e = {{nullptr, nullptr, nullptr, nullptr}};
+    return e;
+}
+}  // namespace diloco
+
 namespace {
 
 // Segment offsets travel to the device inside kernel arguments (no staging copy, no host
@@ -68,8 +75,10 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     p.seg = (const uint64_t*)(ws + L.seg);
     p.stats = (double*)(ws + L.stats);
     p.pivot = (float*)(ws + L.pivot);
-    p.hsum = (double*)(ws + L.hsum);
+    p.hsumq = (unsigned long long*)(ws + L.hsumq);
     p.hcnt = (unsigned long long*)(ws + L.hcnt);
+    p.osum = (double*)(ws + L.osum);
+    p.ocnt = (unsigned long long*)(ws + L.ocnt);
     p.stream = stream;
     int32_t rc = num_compute_units(&p.num_cus);
     if (rc) return rc;
@@ -89,8 +98,8 @@ hipError_t finalize_qparams(const Pass& p, diloco_qparams* qp) {
 }
 
 hipError_t finalize_lut(const Pass& p, const diloco_qparams* qp, float* lut) {
-    hipLaunchKernelGGL(finalize_lut_kernel, dim3(p.T), dim3(kThreads), 0, p.stream, p.T, qp, p.hsum, p.hcnt,
-                       lut);
+    hipLaunchKernelGGL(finalize_lut_kernel, dim3(p.T), dim3(kThreads), 0, p.stream, p.T, qp, p.hsumq, p.hcnt,
+                       p.osum, p.ocnt, lut);
     return hipGetLastError();
 }
 
@@ -102,18 +111,24 @@ hipError_t run_stats(const Src& src, const Pass& p) {
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, false>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
                        g.per_block, p.stats, p.pivot, (float*)nullptr);
-    return hipGetLastError();
+    e = hipGetLastError();
+    (void)mark(1, p.stream);
+    return e;
 }
 
 template <class Src>
 hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     constexpr auto kernel = quant_kernel<Src>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
-                       g.per_block, qp, codes, p.hsum, p.hcnt);
-    return hipGetLastError();
+                       g.per_block, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
+    hipError_t e = hipGetLastError();
+    (void)mark(3, p.stream);
+    return e;
 }
 
 hipError_t reduce_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
@@ -144,6 +159,7 @@ template <int kOut>
 hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t* codes, const float* lut,
                      const uint64_t* seg, uint32_t T, uint64_t N, float lr, float beta, void* local_out,
                      int num_cus, hipStream_t stream) {
+    (void)mark(0, stream);
     if (delta) {
         constexpr auto kernel = outer_fp32_kernel<kOut>;
         Grid g = plan_grid(N, num_cus, resident_blocks_per_cu<kernel>());
@@ -155,7 +171,9 @@ hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, codes, lut, seg, T,
                            N, g.per_block, lr, beta, local_out);
     }
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    (void)mark(1, stream);
+    return e;
 }
 
 }  // namespace
@@ -165,6 +183,12 @@ extern "C" {
 size_t diloco_workspace_bytes(uint32_t T) {
     if (T == 0 || T > DILOCO_MAX_SEGMENTS) return 0;
     return workspace_layout(T).total;
+}
+
+int32_t diloco_profile_passes(void* const* events) {
+    PassEvents& pe = pass_events();
+    for (int i = 0; i < 4; ++i) pe.ev[i] = events ? (hipEvent_t)events[i] : nullptr;
+    return DILOCO_OK;
 }
 
 const char* diloco_strerror(int32_t code) {

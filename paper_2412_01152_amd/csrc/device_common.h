@@ -14,7 +14,14 @@ constexpr int kVec = 4;                             // consecutive elements per 
 constexpr int kUnroll = 4;                          // loads in flight per stream per lane
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
-constexpr int kFlushIters = 8;                      // LDS fp32 bucket sums move to fp64 this often
+// Fixed-point bucket sums: a 64-bit LDS bin holds {count : 24 bits, sum of biased offsets : 40 bits}.
+// An offset is at most one bucket width, scaled by 2^22 / width, so a biased addend is below 2^24
+// and a bin takes 2^16 of them before the low field could carry into the count.
+constexpr int kOffsetBits = 22;
+constexpr int kOffsetBias = 1 << 23;
+constexpr int kCountShift = 40;
+constexpr int kFlushIters = 16;                     // 16 * kIter = 2^16 elements between drains
+static_assert((long long)kFlushIters * kIter * (2ll << 23) <= (1ll << kCountShift), "bin overflow");
 
 // Vector types that promise only element alignment: gfx950 global memory instructions accept
 // any byte address, so one dwordx4 / dwordx2 / dword access is emitted whatever the pointer's
@@ -119,10 +126,16 @@ __device__ __forceinline__ float bucket_width(float inv_w) {
 __device__ __forceinline__ float bucket_centre(int k, float lo, float w) {
     return __fmaf_rn((float)k + 0.5f, w, lo);
 }
+// Factor that turns an offset from the bucket centre into fixed point: 2^22 / width (0 when the
+// segment is degenerate or the factor would overflow; then every non-zero offset goes the fp64 way).
+__device__ __forceinline__ float offset_scale(float inv_w) {
+    const float s = __fmul_rn(inv_w, (float)(1 << kOffsetBits));
+    return (inv_w > 0.0f && s <= 3.0e38f) ? s : 0.0f;
+}
 
 // Device scratch layout (all offsets in bytes from a 256-byte aligned base).
 struct WorkspaceLayout {
-    size_t seg, stats, pivot, hsum, hcnt, total;
+    size_t seg, stats, pivot, hsumq, hcnt, osum, ocnt, total;
 };
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 __host__ inline WorkspaceLayout workspace_layout(uint32_t T) {
@@ -134,10 +147,14 @@ __host__ inline WorkspaceLayout workspace_layout(uint32_t T) {
     o = align_up(o + sizeof(double) * 2 * (size_t)T, 256);
     L.pivot = o;
     o = align_up(o + sizeof(float) * (size_t)T, 256);
-    L.hsum = o;
-    o = align_up(o + sizeof(double) * kBuckets * (size_t)T, 256);
+    L.hsumq = o;
+    o = align_up(o + sizeof(unsigned long long) * kBuckets * (size_t)T, 256);
     L.hcnt = o;
     o = align_up(o + sizeof(unsigned long long) * kBuckets * (size_t)T, 256);
+    L.osum = o;
+    o = align_up(o + sizeof(double) * 2 * (size_t)T, 256);
+    L.ocnt = o;
+    o = align_up(o + sizeof(unsigned long long) * 2 * (size_t)T, 256);
     L.total = o;
     return L;
 }

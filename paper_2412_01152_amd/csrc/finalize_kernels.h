@@ -51,23 +51,33 @@ __global__ void finalize_qparams_kernel(const uint64_t* __restrict__ seg, uint32
     qp[s] = r;
 }
 
-// Item 4 of Section 2.2: codebook entry = average of the values in the bucket.  The bins hold sums
-// of (x - centre), so the centre is added back in fp64.  An empty bucket gets its midpoint.
+// Item 4 of Section 2.2: codebook entry = average of the values in the bucket.  The bins hold
+// integer sums of scaled offsets from the bucket centre (plus, for buckets 0 and 255, fp64 sums of
+// the far clipped values), so the average offset is rebuilt in fp64 and the centre added back.
+// An empty bucket gets its midpoint.
 __global__ __launch_bounds__(kThreads) void finalize_lut_kernel(uint32_t T,
                                                                const diloco_qparams* __restrict__ qp,
-                                                               const double* __restrict__ hsum,
+                                                               const unsigned long long* __restrict__ hsumq,
                                                                const unsigned long long* __restrict__ hcnt,
+                                                               const double* __restrict__ osum,
+                                                               const unsigned long long* __restrict__ ocnt,
                                                                float* __restrict__ lut) {
     const uint32_t s = blockIdx.x;
     const int k = threadIdx.x;
     if (s >= T) return;
     const diloco_qparams q = qp[s];
-    const unsigned long long c = hcnt[(size_t)s * kBuckets + k];
+    unsigned long long c = hcnt[(size_t)s * kBuckets + k];
+    const float w = bucket_width(q.inv_w);
+    const float scale = offset_scale(q.inv_w);
+    double off_sum = scale > 0.0f ? (double)(long long)hsumq[(size_t)s * kBuckets + k] / (double)scale : 0.0;
+    if (k == 0 || k == kBuckets - 1) {
+        const int e = k == 0 ? 0 : 1;
+        c += ocnt[2 * (size_t)s + e];
+        off_sum += osum[2 * (size_t)s + e];
+    }
     float out;
     if (c > 0) {
-        const float w = bucket_width(q.inv_w);
-        const double centre = (double)bucket_centre(k, q.lo, w);
-        out = (float)(centre + hsum[(size_t)s * kBuckets + k] / (double)c);
+        out = (float)((double)bucket_centre(k, q.lo, w) + off_sum / (double)c);
     } else {
         const double lo64 = q.mean - 6.0 * q.std;
         const double w64 = 12.0 * q.std / 256.0;

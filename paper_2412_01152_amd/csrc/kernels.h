@@ -3,7 +3,7 @@
 // Section 2.2's quantiser needs the statistics of a whole segment before any element can be coded,
 // so every quantising call is two streaming passes over its input:
 //   pass A  (stats_kernel)  values -> per-segment sum and sum of squares about a pivot, in fp64
-//   pass B  (quant_kernel)  values -> bucket index per element + per-bucket {count, sum}
+//   pass B  (quant_kernel)  values -> bucket index per element + per-bucket {count, offset sum}
 // with two tiny kernels between and after them that turn the sums into (lo, 1/width) and into the
 // codebook.  "Values" come from a source functor: the pseudo-gradient theta_outer - theta_local
 // (stage 1), the averaged fp32 sum of decoded peer contributions (stage 2), or a stored fp32 array.
@@ -218,20 +218,69 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint6
 // ------------------------------------------------------------------------------------------
 // pass B: bucket index per element, and the per-bucket sums behind the codebook (item 4)
 // ------------------------------------------------------------------------------------------
-// One LDS histogram of {count, fp32 sum of (x - bucket centre)} per block, fed by LDS atomics.
-// Thread k owns bucket k: every kFlushIters iterations it moves the bucket's LDS partial into
-// fp64 registers (bounding the fp32 accumulation error), and when the block leaves the segment
-// it adds its totals to the segment's global bins with one fp64 and one integer atomic.
+// The codebook needs, per bucket, the count and the sum of the values in it.  Floating-point LDS
+// atomics are several times slower than integer ones on this chip, so the sum is kept in fixed
+// point: for a value x in bucket k the kernel forms off = x - centre_k (|off| <= half a bucket),
+// q = round(off * 2^22 / width), and adds the single 64-bit word  (1 << 40) | (q + 2^23)  to the
+// bucket's LDS bin: count in the top 24 bits, biased offset sum in the low 40.  One rounding of at
+// most 0.75 * 2^-22 of a bucket per element, integer sums exact and order-independent thereafter.
+// Values further than one bucket width from their bucket's centre (the clipped tails that land in
+// buckets 0 and 255) do not fit that format; they are rare and go through per-thread fp64
+// accumulators instead.  Thread k owns bin k: every kFlushIters iterations (before the 40-bit field
+// can overflow) it moves the bin into 64-bit registers, and when the block leaves the segment it
+// adds its totals to the segment's global integer bins.
+struct PassBOut {
+    unsigned long long* hsumq;   // [T][256] signed sum of q (two's complement)
+    unsigned long long* hcnt;    // [T][256]
+    double* osum;                // [T][2]   fp64 sum of off of the far values in bucket 0 / 255
+    unsigned long long* ocnt;    // [T][2]
+};
+
+struct BinScale {
+    float lo, inv_w, w, scale, reach;
+};
+__device__ __forceinline__ BinScale bin_scale(float lo, float inv_w) {
+    BinScale b;
+    b.lo = lo;
+    b.inv_w = inv_w;
+    b.w = bucket_width(inv_w);
+    b.scale = offset_scale(inv_w);
+    b.reach = b.scale > 0.0f ? b.w : 0.0f;   // no fixed-point scale: only exact zeros take the fast path
+    return b;
+}
+
+struct FarSums {
+    double lo_sum = 0.0, hi_sum = 0.0;
+    unsigned lo_cnt = 0, hi_cnt = 0;
+};
+
+__device__ __forceinline__ int code_and_bin(float x, const BinScale& b, unsigned long long* s_bin,
+                                            FarSums& far) {
+    const int k = bucket_of(x, b.lo, b.inv_w);
+    const float off = __fsub_rn(x, bucket_centre(k, b.lo, b.w));
+    if (!(fabsf(off) <= b.reach)) {
+        if (k == 0) {          // a value below the range is clipped into bucket 0, everything else
+            far.lo_sum += (double)off;   // that is far from its centre sits in bucket 255
+            far.lo_cnt += 1;
+        } else {
+            far.hi_sum += (double)off;
+            far.hi_cnt += 1;
+        }
+    } else {
+        const unsigned q = (unsigned)(__float2int_rn(__fmul_rn(off, b.scale)) + kOffsetBias);
+        atomicAdd(&s_bin[k], (1ull << kCountShift) | (unsigned long long)q);
+    }
+    return k;
+}
+
 template <class Src>
 __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, uint64_t per_block,
                                                         const diloco_qparams* __restrict__ qp,
-                                                        uint8_t* __restrict__ codes,
-                                                        double* __restrict__ hsum,
-                                                        unsigned long long* __restrict__ hcnt) {
+                                                        uint8_t* __restrict__ codes, PassBOut out) {
     __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
-    __shared__ unsigned s_cnt[kBuckets];
-    __shared__ float s_sum[kBuckets];
+    __shared__ unsigned long long s_bin[kBuckets];
+    __shared__ double s_red[8];
     Src src = src_in;
     src.bind(s_src);
     const Share sh = block_share(N, per_block);
@@ -247,14 +296,18 @@ __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint6
         }
         const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
         src.enter_segment(s);
-        const float lo = qp[s].lo;
-        const float inv_w = qp[s].inv_w;
-        const float w = bucket_width(inv_w);
-        double bin_sum = 0.0;
-        unsigned long long bin_cnt = 0;
-        s_cnt[tid] = 0;
-        s_sum[tid] = 0.0f;
+        const BinScale bs = bin_scale(qp[s].lo, qp[s].inv_w);
+        long long bin_q = 0;
+        unsigned long long bin_c = 0;
+        FarSums far;
+        s_bin[tid] = 0;
         __syncthreads();
+        auto drain = [&]() {
+            const unsigned long long packed = s_bin[tid];
+            const unsigned long long c = packed >> kCountShift;
+            bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kOffsetBias;
+            bin_c += c;
+        };
         uint64_t base = pos;
         int since_flush = 0;
         for (; base + kIter <= sub_end; base += kIter) {
@@ -267,37 +320,40 @@ __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint6
                 f32x4 v = src.value4(raw[j]);
                 uint32_t packed = 0;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    int k = bucket_of(v[e], lo, inv_w);
-                    atomicAdd(&s_cnt[k], 1u);
-                    atomicAdd(&s_sum[k], __fsub_rn(v[e], bucket_centre(k, lo, w)));
-                    packed |= (uint32_t)k << (8 * e);
-                }
+                for (int e = 0; e < 4; ++e)
+                    packed |= (uint32_t)code_and_bin(v[e], bs, s_bin, far) << (8 * e);
                 st_u8x4(codes + base + (uint64_t)(j * kThreads + tid) * kVec, packed);
             }
             if (++since_flush == kFlushIters) {
                 since_flush = 0;
                 __syncthreads();
-                bin_sum += (double)s_sum[tid];
-                bin_cnt += s_cnt[tid];
-                s_sum[tid] = 0.0f;
-                s_cnt[tid] = 0;
+                drain();
+                s_bin[tid] = 0;
                 __syncthreads();
             }
         }
-        for (uint64_t i = base + tid; i < sub_end; i += kThreads) {
-            float v = src.value1(i);
-            int k = bucket_of(v, lo, inv_w);
-            atomicAdd(&s_cnt[k], 1u);
-            atomicAdd(&s_sum[k], __fsub_rn(v, bucket_centre(k, lo, w)));
-            codes[i] = (uint8_t)k;
-        }
+        for (uint64_t i = base + tid; i < sub_end; i += kThreads)
+            codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, far);
         __syncthreads();
-        bin_sum += (double)s_sum[tid];
-        bin_cnt += s_cnt[tid];
-        if (bin_cnt) {
-            atomicAdd(&hsum[(size_t)s * kBuckets + tid], bin_sum);
-            atomicAdd(&hcnt[(size_t)s * kBuckets + tid], bin_cnt);
+        drain();
+        if (bin_c) {
+            atomicAdd(&out.hsumq[(size_t)s * kBuckets + tid], (unsigned long long)bin_q);
+            atomicAdd(&out.hcnt[(size_t)s * kBuckets + tid], bin_c);
+        }
+        if (__syncthreads_or((int)(far.lo_cnt | far.hi_cnt))) {
+            double c_lo = (double)far.lo_cnt, c_hi = (double)far.hi_cnt;
+            block_sum2(far.lo_sum, far.hi_sum, s_red);
+            block_sum2(c_lo, c_hi, s_red);
+            if (tid == 0) {
+                if (c_lo > 0.0) {
+                    atomicAdd(&out.osum[2 * (size_t)s], far.lo_sum);
+                    atomicAdd(&out.ocnt[2 * (size_t)s], (unsigned long long)c_lo);
+                }
+                if (c_hi > 0.0) {
+                    atomicAdd(&out.osum[2 * (size_t)s + 1], far.hi_sum);
+                    atomicAdd(&out.ocnt[2 * (size_t)s + 1], (unsigned long long)c_hi);
+                }
+            }
         }
         pos = sub_end;
     }

@@ -15,8 +15,10 @@ struct Pass {
     const uint64_t* seg;        // device, [T+1]
     double* stats;              // device, [T][2]
     float* pivot;               // device, [T]
-    double* hsum;               // device, [T][256]
+    unsigned long long* hsumq;  // device, [T][256]
     unsigned long long* hcnt;   // device, [T][256]
+    double* osum;               // device, [T][2]
+    unsigned long long* ocnt;   // device, [T][2]
     int num_cus;
     hipStream_t stream;
 };
@@ -29,6 +31,17 @@ struct ReduceArgs {
     float div;
     int div_mode;
 };
+
+// Optional HIP events recorded around the streaming passes (benchmark instrumentation); all null
+// unless the calling thread asked for them.
+struct PassEvents {
+    hipEvent_t ev[4];
+};
+PassEvents& pass_events();
+inline hipError_t mark(int which, hipStream_t stream) {
+    hipEvent_t e = pass_events().ev[which];
+    return e ? hipEventRecord(e, stream) : hipSuccess;
+}
 
 // Resident blocks per compute unit of a kernel, looked up once per process.
 template <auto Kernel>

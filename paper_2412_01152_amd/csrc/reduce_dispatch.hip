@@ -35,9 +35,12 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, kWriteAcc>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal>(a), p.seg,
                        p.T, p.N, g.per_block, p.stats, p.pivot, acc_out);
-    return hipGetLastError();
+    e = hipGetLastError();
+    (void)mark(1, p.stream);
+    return e;
 }
 
 template <int W, bool kLocal>
@@ -45,9 +48,12 @@ hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* q
     using Src = SrcReduce<W, kLocal>;
     constexpr auto kernel = quant_kernel<Src>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal>(a), p.seg,
-                       p.T, p.N, g.per_block, qp, codes, p.hsum, p.hcnt);
-    return hipGetLastError();
+                       p.T, p.N, g.per_block, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
+    hipError_t e = hipGetLastError();
+    (void)mark(3, p.stream);
+    return e;
 }
 
 template <int W>
