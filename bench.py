@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration (0, 1 or 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 2^28 fp32 (1 GiB read, 1 GiB written) so that "
+                         "profiler byte counters can be scaled against a kernel of known traffic")
     ap.add_argument("--traffic-kib", type=float, default=None,
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (optional)")
     args = ap.parse_args()
@@ -118,6 +121,14 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        n_cal = 1 << 28                      # 1 GiB read + 1 GiB written, one launch
+        src = local[:n_cal]
+        dst = torch.empty(n_cal, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            torch.neg(src, out=dst)          # the only negation kernel in the run: easy to find
+        torch.cuda.synchronize()
+        del dst
 
     # HIP events: created by torch (one dummy record makes the handle exist), recorded by the library
     def make_events():

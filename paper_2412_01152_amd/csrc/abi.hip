@@ -261,14 +261,11 @@ int32_t int8_reduce_chunk(const uint8_t* const* peer_codes, const float* const* 
         misaligned(qparams_out, 8))
         return DILOCO_ERR_ALIGN;
     a.local = local_fp32;
-    if (divisor == 1) {
-        a.div_mode = kDivNone;
-        a.div = 1.0f;
-    } else if ((divisor & (divisor - 1)) == 0) {
-        a.div_mode = kDivPow2;       // multiplying by 2^-j rounds exactly like dividing by 2^j
+    if ((divisor & (divisor - 1)) == 0) {
+        a.true_div = false;          // multiplying by 2^-j rounds exactly like dividing by 2^j
         a.div = 1.0f / (float)divisor;
     } else {
-        a.div_mode = kDivTrue;
+        a.true_div = true;
         a.div = (float)divisor;
     }
     Pass p;

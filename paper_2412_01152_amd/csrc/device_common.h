@@ -15,13 +15,14 @@ constexpr int kUnroll = 4;                          // loads in flight per strea
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
 // Fixed-point bucket sums: a 64-bit LDS bin holds {count : 24 bits, sum of biased offsets : 40 bits}.
-// An offset is at most one bucket width, scaled by 2^22 / width, so a biased addend is below 2^24
-// and a bin takes 2^16 of them before the low field could carry into the count.
-constexpr int kOffsetBits = 22;
-constexpr int kOffsetBias = 1 << 23;
+// An offset is at most one bucket width, scaled by 2^21 / width and biased by 2^22, so an addend is
+// below 2^23 and a bin takes 2^17 of them before the low field could carry into the count.
+constexpr int kOffsetBits = 21;
+constexpr int kOffsetBias = 1 << 22;
+constexpr float kRoundMagic = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer
 constexpr int kCountShift = 40;
 constexpr int kFlushIters = 16;                     // 16 * kIter = 2^16 elements between drains
-static_assert((long long)kFlushIters * kIter * (2ll << 23) <= (1ll << kCountShift), "bin overflow");
+static_assert((long long)(kFlushIters + 1) * kIter * (1ll << 23) <= (1ll << kCountShift), "bin overflow");
 
 // Vector types that promise only element alignment: gfx950 global memory instructions accept
 // any byte address, so one dwordx4 / dwordx2 / dword access is emitted whatever the pointer's
@@ -106,25 +107,22 @@ __device__ __forceinline__ void block_sum2(double& a, double& b, double* red) {
     }
 }
 
-// Bucket index of Section 2.2's quantiser: floor((x - lo) / width) clipped to [0, 255], with the
-// subtraction and the multiplication by the reciprocal width as two separately rounded fp32
-// operations (never contracted into a fused multiply-add).  NaN goes to bucket 0.
-__device__ __forceinline__ int bucket_of(float x, float lo, float inv_w) {
-    float t = __fmul_rn(__fsub_rn(x, lo), inv_w);
-    int k = (int)t;
-    k = t >= 255.0f ? 255 : k;
-    k = !(t > 0.0f) ? 0 : k;
-    return k;
-}
-
 // fp32 bucket width and bucket centre used for the codebook sums: the kernel accumulates
 // (x - centre_k), whose magnitude is half a bucket, instead of x; the finalising kernel adds
 // centre_k back in fp64.  Both must use exactly these two functions.
 __device__ __forceinline__ float bucket_width(float inv_w) {
     return inv_w > 0.0f ? __fdiv_rn(1.0f, inv_w) : 0.0f;
 }
-__device__ __forceinline__ float bucket_centre(int k, float lo, float w) {
-    return __fmaf_rn((float)k + 0.5f, w, lo);
+__device__ __forceinline__ float bucket_centre(float kf, float lo, float w) {
+    return __fmaf_rn(kf + 0.5f, w, lo);
+}
+// Bucket index of Section 2.2's quantiser, as a float (0.0 .. 255.0): floor((x - lo) / width)
+// clipped to [0, 255], with the subtraction and the multiplication by the reciprocal width as two
+// separately rounded fp32 operations (never contracted into a fused multiply-add).  Anything <= 0
+// or NaN clamps to bucket 0, anything >= 255 to bucket 255.
+__device__ __forceinline__ float bucket_of_f(float x, float lo, float inv_w) {
+    const float t = __fmul_rn(__fsub_rn(x, lo), inv_w);
+    return __builtin_amdgcn_fmed3f(__builtin_floorf(t), 0.0f, 255.0f);
 }
 // Factor that turns an offset from the bucket centre into fixed point: 2^22 / width (0 when the
 // segment is degenerate or the factor would overflow; then every non-zero offset goes the fp64 way).

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void finalize_lut_kernel(uint32_t T,
     }
     float out;
     if (c > 0) {
-        out = (float)((double)bucket_centre(k, q.lo, w) + off_sum / (double)c);
+        out = (float)((double)bucket_centre((float)k, q.lo, w) + off_sum / (double)c);
     } else {
         const double lo64 = q.mean - 6.0 * q.std;
         const double w64 = 12.0 * q.std / 256.0;

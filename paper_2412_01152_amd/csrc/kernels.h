@@ -74,16 +74,16 @@ struct SrcF32 {
 // Section 2.2's reduction: decode each of the W coded contributions through its segment's
 // codebook (held in LDS), add them in contribution order in fp32 on top of the optional
 // un-quantised local value, then take the average of Algorithm 1 (division by k).
-enum DivMode { kDivNone = 0, kDivPow2 = 1, kDivTrue = 2 };
-
-template <int W, bool kHasLocal>
+// The average is a compile-time choice between two forms: multiplication by `div` (used when the
+// divisor is a power of two, 1 included: the product rounds exactly like the quotient) and a true
+// correctly rounded fp32 division by `div`.
+template <int W, bool kHasLocal, bool kTrueDiv>
 struct SrcReduce {
     static constexpr int kW = W > 0 ? W : 1;
     const uint8_t* codes[kW];
     const float* luts[kW];     // each [T][256]
     const float* local;        // [n] or nullptr
-    float div;                 // divisor, or its exact reciprocal when it is a power of two
-    int div_mode;
+    float div;                 // the divisor (kTrueDiv) or its exact reciprocal
     float* lds;                // W tables of 256 floats
     static constexpr int kLdsFloats = W * kBuckets;
     struct Raw {
@@ -101,9 +101,7 @@ struct SrcReduce {
         }
     }
     __device__ __forceinline__ float finish(float v) const {
-        if (div_mode == kDivPow2) return __fmul_rn(v, div);
-        if (div_mode == kDivTrue) return __fdiv_rn(v, div);
-        return v;
+        return kTrueDiv ? __fdiv_rn(v, div) : __fmul_rn(v, div);
     }
     __device__ __forceinline__ Raw fetch4(uint64_t i) const {
         Raw r;
@@ -221,9 +219,9 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint6
 // The codebook needs, per bucket, the count and the sum of the values in it.  Floating-point LDS
 // atomics are several times slower than integer ones on this chip, so the sum is kept in fixed
 // point: for a value x in bucket k the kernel forms off = x - centre_k (|off| <= half a bucket),
-// q = round(off * 2^22 / width), and adds the single 64-bit word  (1 << 40) | (q + 2^23)  to the
+// q = round(off * 2^21 / width), and adds the single 64-bit word  (1 << 40) | (q + 2^22)  to the
 // bucket's LDS bin: count in the top 24 bits, biased offset sum in the low 40.  One rounding of at
-// most 0.75 * 2^-22 of a bucket per element, integer sums exact and order-independent thereafter.
+// most 2^-22 of a bucket per element, integer sums exact and order-independent thereafter.
 // Values further than one bucket width from their bucket's centre (the clipped tails that land in
 // buckets 0 and 255) do not fit that format; they are rare and go through per-thread fp64
 // accumulators instead.  Thread k owns bin k: every kFlushIters iterations (before the 40-bit field
@@ -256,8 +254,9 @@ struct FarSums {
 
 __device__ __forceinline__ int code_and_bin(float x, const BinScale& b, unsigned long long* s_bin,
                                             FarSums& far) {
-    const int k = bucket_of(x, b.lo, b.inv_w);
-    const float off = __fsub_rn(x, bucket_centre(k, b.lo, b.w));
+    const float kf = bucket_of_f(x, b.lo, b.inv_w);
+    const int k = (int)(unsigned)kf & (kBuckets - 1);
+    const float off = __fsub_rn(x, bucket_centre(kf, b.lo, b.w));
     if (!(fabsf(off) <= b.reach)) {
         if (k == 0) {          // a value below the range is clipped into bucket 0, everything else
             far.lo_sum += (double)off;   // that is far from its centre sits in bucket 255
@@ -267,7 +266,8 @@ __device__ __forceinline__ int code_and_bin(float x, const BinScale& b, unsigned
             far.hi_cnt += 1;
         }
     } else {
-        const unsigned q = (unsigned)(__float2int_rn(__fmul_rn(off, b.scale)) + kOffsetBias);
+        // round(off * scale) + 2^22 read off the mantissa of (off * scale + 1.5 * 2^23)
+        const unsigned q = __float_as_uint(__fmaf_rn(off, b.scale, kRoundMagic)) & 0x7fffffu;
         atomicAdd(&s_bin[k], (1ull << kCountShift) | (unsigned long long)q);
     }
     return k;

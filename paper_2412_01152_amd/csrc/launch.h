@@ -28,8 +28,8 @@ struct ReduceArgs {
     const float* luts[DILOCO_MAX_PEERS];
     uint32_t W;
     const float* local;
-    float div;
-    int div_mode;
+    float div;        // divisor (true_div) or its exact reciprocal
+    bool true_div;
 };
 
 // Optional HIP events recorded around the streaming passes (benchmark instrumentation); all null

@@ -12,69 +12,74 @@
 namespace diloco {
 namespace {
 
-template <int W, bool kLocal>
-SrcReduce<W, kLocal> make_src(const ReduceArgs& a) {
-    SrcReduce<W, kLocal> s;
-    for (int p = 0; p < SrcReduce<W, kLocal>::kW; ++p) {
+template <int W, bool kLocal, bool kTrueDiv>
+SrcReduce<W, kLocal, kTrueDiv> make_src(const ReduceArgs& a) {
+    SrcReduce<W, kLocal, kTrueDiv> s;
+    for (int p = 0; p < SrcReduce<W, kLocal, kTrueDiv>::kW; ++p) {
         s.codes[p] = p < W ? a.codes[p] : nullptr;
         s.luts[p] = p < W ? a.luts[p] : nullptr;
     }
     s.local = a.local;
     s.div = a.div;
-    s.div_mode = a.div_mode;
     s.lds = nullptr;
     return s;
 }
 
-template <int W, bool kLocal, bool kWriteAcc>
+template <int W, bool kLocal, bool kTrueDiv, bool kWriteAcc>
 hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
-    using Src = SrcReduce<W, kLocal>;
+    using Src = SrcReduce<W, kLocal, kTrueDiv>;
     hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + 255) / 256), dim3(256), 0, p.stream,
-                       make_src<W, kLocal>(a), p.seg, p.T, p.pivot);
+                       make_src<W, kLocal, kTrueDiv>(a), p.seg, p.T, p.pivot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, kWriteAcc>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
     (void)mark(0, p.stream);
-    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal>(a), p.seg,
+    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.per_block, p.stats, p.pivot, acc_out);
     e = hipGetLastError();
     (void)mark(1, p.stream);
     return e;
 }
 
-template <int W, bool kLocal>
+template <int W, bool kLocal, bool kTrueDiv>
 hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
-    using Src = SrcReduce<W, kLocal>;
+    using Src = SrcReduce<W, kLocal, kTrueDiv>;
     constexpr auto kernel = quant_kernel<Src>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
     (void)mark(2, p.stream);
-    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal>(a), p.seg,
+    hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.per_block, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
 }
 
+template <int W, bool kLocal, bool kTrueDiv>
+hipError_t stats_wld(const ReduceArgs& a, const Pass& p, float* acc_out) {
+    return acc_out ? run_stats<W, kLocal, kTrueDiv, true>(a, p, acc_out)
+                   : run_stats<W, kLocal, kTrueDiv, false>(a, p, acc_out);
+}
+
 template <int W>
 hipError_t stats_w(const ReduceArgs& a, const Pass& p, float* acc_out) {
-    if (a.local) {
-        return acc_out ? run_stats<W, true, true>(a, p, acc_out) : run_stats<W, true, false>(a, p, acc_out);
-    }
+    if (a.local)
+        return a.true_div ? stats_wld<W, true, true>(a, p, acc_out) : stats_wld<W, true, false>(a, p, acc_out);
     if constexpr (W == 0)
         return hipErrorInvalidValue;
     else
-        return acc_out ? run_stats<W, false, true>(a, p, acc_out)
-                       : run_stats<W, false, false>(a, p, acc_out);
+        return a.true_div ? stats_wld<W, false, true>(a, p, acc_out) : stats_wld<W, false, false>(a, p, acc_out);
 }
 
 template <int W>
 hipError_t quant_w(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
-    if (a.local) return run_quant<W, true>(a, p, qp, codes);
+    if (a.local)
+        return a.true_div ? run_quant<W, true, true>(a, p, qp, codes) : run_quant<W, true, false>(a, p, qp, codes);
     if constexpr (W == 0)
         return hipErrorInvalidValue;
     else
-        return run_quant<W, false>(a, p, qp, codes);
+        return a.true_div ? run_quant<W, false, true>(a, p, qp, codes)
+                          : run_quant<W, false, false>(a, p, qp, codes);
 }
 
 }  // namespace
