@@ -29,9 +29,12 @@ UNITS = [("abi.o", "abi.hip", []),
          ("reduce_g3.o", "reduce_dispatch.hip", ["-DDILOCO_W_GROUP=3"])]
 
 
+EXTRA = os.environ.get("DILOCO_EXTRA_FLAGS", "").split()
+
+
 def _compile(unit):
     obj, src, defs = unit
-    cmd = [HIPCC, *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(BUILD, obj)]
+    cmd = [HIPCC, *FLAGS, *EXTRA, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(BUILD, obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     return unit, r
 

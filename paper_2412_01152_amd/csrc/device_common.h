@@ -11,7 +11,19 @@ namespace diloco {
 
 constexpr int kThreads = 256;                       // 4 wave64 per block; also the number of buckets
 constexpr int kVec = 4;                             // consecutive elements per lane per load
-constexpr int kUnroll = 4;                          // loads in flight per stream per lane
+#ifndef DILOCO_UNROLL
+#define DILOCO_UNROLL 4
+#endif
+#ifndef DILOCO_COPIES_STREAM
+#define DILOCO_COPIES_STREAM 1      // bin copies in pass B of the memory-bound sources
+#endif
+#ifndef DILOCO_COPIES_REDUCE
+#define DILOCO_COPIES_REDUCE 16     // bin copies in pass B of the LDS-bound reduce source
+#endif
+#ifndef DILOCO_MIN_WAVES
+#define DILOCO_MIN_WAVES 1
+#endif
+constexpr int kUnroll = DILOCO_UNROLL;              // loads in flight per stream per lane
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
 // Fixed-point bucket sums: a 64-bit LDS bin holds {count : 24 bits, sum of biased offsets : 40 bits}.

@@ -155,7 +155,7 @@ __global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t
 }
 
 template <class Src, bool kWriteAcc>
-__global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint64_t* __restrict__ seg,
+__global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, uint64_t per_block,
                                                         double* __restrict__ stats,
                                                         const float* __restrict__ pivot,
@@ -252,40 +252,77 @@ struct FarSums {
     unsigned lo_cnt = 0, hi_cnt = 0;
 };
 
+__device__ __forceinline__ void far_add(float off, int k, FarSums& far) {
+    if (k == 0) {              // a value below the range is clipped into bucket 0, everything else
+        far.lo_sum += (double)off;   // that is far from its centre sits in bucket 255
+        far.lo_cnt += 1;
+    } else {
+        far.hi_sum += (double)off;
+        far.hi_cnt += 1;
+    }
+}
+
 __device__ __forceinline__ int code_and_bin(float x, const BinScale& b, unsigned long long* s_bin,
-                                            FarSums& far) {
+                                            int copies, FarSums& far) {
     const float kf = bucket_of_f(x, b.lo, b.inv_w);
     const int k = (int)(unsigned)kf & (kBuckets - 1);
     const float off = __fsub_rn(x, bucket_centre(kf, b.lo, b.w));
     if (!(fabsf(off) <= b.reach)) {
-        if (k == 0) {          // a value below the range is clipped into bucket 0, everything else
-            far.lo_sum += (double)off;   // that is far from its centre sits in bucket 255
-            far.lo_cnt += 1;
-        } else {
-            far.hi_sum += (double)off;
-            far.hi_cnt += 1;
-        }
+        far_add(off, k, far);
     } else {
         // round(off * scale) + 2^22 read off the mantissa of (off * scale + 1.5 * 2^23)
         const unsigned q = __float_as_uint(__fmaf_rn(off, b.scale, kRoundMagic)) & 0x7fffffu;
-        atomicAdd(&s_bin[k], (1ull << kCountShift) | (unsigned long long)q);
+        atomicAdd(&s_bin[k * copies], (1ull << kCountShift) | (unsigned long long)q);
     }
     return k;
 }
 
-template <class Src>
-__global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
+// Four values at once: the four index / offset chains are independent, the bin updates are
+// predicated, and the rare far values of the group are handled behind a single branch.
+__device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, unsigned long long* s_bin,
+                                                  int copies, FarSums& far) {
+    int k[4];
+    float off[4];
+    bool is_far[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float kf = bucket_of_f(v[e], b.lo, b.inv_w);
+        k[e] = (int)(unsigned)kf & (kBuckets - 1);
+        off[e] = __fsub_rn(v[e], bucket_centre(kf, b.lo, b.w));
+        is_far[e] = !(fabsf(off[e]) <= b.reach);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (!is_far[e]) {
+            const unsigned q = __float_as_uint(__fmaf_rn(off[e], b.scale, kRoundMagic)) & 0x7fffffu;
+            atomicAdd(&s_bin[k[e] * copies], (1ull << kCountShift) | (unsigned long long)q);
+        }
+    }
+    if (is_far[0] | is_far[1] | is_far[2] | is_far[3]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (is_far[e]) far_add(off[e], k[e], far);
+    }
+    return (uint32_t)k[0] | ((uint32_t)k[1] << 8) | ((uint32_t)k[2] << 16) | ((uint32_t)k[3] << 24);
+}
+
+// kCopies: each bucket's LDS bin exists kCopies times, copy (lane mod kCopies) at consecutive
+// addresses, so that neighbouring lanes hit different banks even when they hit the same bucket
+// (a 64-bit bin spans two of the 32 banks; with 16 copies 16 consecutive lanes never collide).
+template <class Src, int kCopies>
+__global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, uint64_t per_block,
                                                         const diloco_qparams* __restrict__ qp,
                                                         uint8_t* __restrict__ codes, PassBOut out) {
     __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
-    __shared__ unsigned long long s_bin[kBuckets];
+    __shared__ unsigned long long s_bin_all[kBuckets * kCopies];
     __shared__ double s_red[8];
     Src src = src_in;
     src.bind(s_src);
     const Share sh = block_share(N, per_block);
     if (sh.begin >= sh.end) return;
     const int tid = threadIdx.x;
+    unsigned long long* const s_bin = s_bin_all + (tid & (kCopies - 1));   // this lane's copy
     uint32_t s = find_segment(seg, T, sh.begin);
     uint64_t pos = sh.begin;
     while (pos < sh.end) {
@@ -300,13 +337,21 @@ __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint6
         long long bin_q = 0;
         unsigned long long bin_c = 0;
         FarSums far;
-        s_bin[tid] = 0;
+#pragma unroll
+        for (int c = 0; c < kCopies; ++c) s_bin_all[c * kBuckets + tid] = 0;
         __syncthreads();
-        auto drain = [&]() {
-            const unsigned long long packed = s_bin[tid];
-            const unsigned long long c = packed >> kCountShift;
-            bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kOffsetBias;
-            bin_c += c;
+        // thread k sums (and clears) the kCopies copies of bin k, starting at a rotated copy so
+        // that the lanes of a wave read different banks
+        auto drain = [&](bool clear) {
+#pragma unroll
+            for (int i = 0; i < kCopies; ++i) {
+                const int idx = tid * kCopies + ((i + tid) & (kCopies - 1));
+                const unsigned long long packed = s_bin_all[idx];
+                if (clear) s_bin_all[idx] = 0;
+                const unsigned long long c = packed >> kCountShift;
+                bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kOffsetBias;
+                bin_c += c;
+            }
         };
         uint64_t base = pos;
         int since_flush = 0;
@@ -317,25 +362,21 @@ __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint6
                 raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
 #pragma unroll
             for (int j = 0; j < kUnroll; ++j) {
-                f32x4 v = src.value4(raw[j]);
-                uint32_t packed = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    packed |= (uint32_t)code_and_bin(v[e], bs, s_bin, far) << (8 * e);
-                st_u8x4(codes + base + (uint64_t)(j * kThreads + tid) * kVec, packed);
+                const f32x4 v = src.value4(raw[j]);
+                st_u8x4(codes + base + (uint64_t)(j * kThreads + tid) * kVec,
+                        code_and_bin4(v, bs, s_bin, kCopies, far));
             }
             if (++since_flush == kFlushIters) {
                 since_flush = 0;
                 __syncthreads();
-                drain();
-                s_bin[tid] = 0;
+                drain(true);
                 __syncthreads();
             }
         }
         for (uint64_t i = base + tid; i < sub_end; i += kThreads)
-            codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, far);
+            codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far);
         __syncthreads();
-        drain();
+        drain(false);
         if (bin_c) {
             atomicAdd(&out.hsumq[(size_t)s * kBuckets + tid], (unsigned long long)bin_q);
             atomicAdd(&out.hcnt[(size_t)s * kBuckets + tid], bin_c);
