@@ -1,0 +1,269 @@
+"""The five benchmark configurations against the oracle (needs an MI355X).
+
+Configurations 0 and 1 run at their full size, element by element.  Configuration 2 (the one
+bench.py times: 10,211,381,248 elements, 381 tensors, W = 4) runs at full size in the benchmark's
+launch configuration and is checked on sampled tensors the oracle can process whole, plus
+properties that hold at any size.  Configurations 3 and 4 keep their structure (14 heavy-tailed
+coded peers with the accumulation stored over theta_local; 14 ring chunks of a size that is not a
+multiple of anything, 13 coded peers + un-quantised local addend, bf16 theta_local) on the first
+attention block's tensors, a size the oracle finishes in seconds.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_01152_amd import synth
+from parity_utils import (bf16_bits, check_codes, check_luts, check_outer, check_qparams, t2n)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+LR, BETA = 0.7, 0.9
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2412_01152_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(autouse=True)
+def _free_gpu():
+    yield
+    torch.cuda.empty_cache()
+
+
+def _decode(codes, luts, off):
+    return np.concatenate([luts[s][codes[off[s]:off[s + 1]]] for s in range(len(off) - 1)])
+
+
+def _full_chain(B, oracle_mod, sizes, W, kind, local_dtype=torch.float32, materialise=False):
+    """Stage-isolated run of the three stages on a workload small enough for the oracle."""
+    theta, locals_, off = synth.make_inputs(sizes, W, kind=kind, device=DEV, local_dtype=local_dtype)
+    n = theta.numel()
+    th = t2n(theta)
+    t0 = time.time()
+    o1 = []
+    for p, l in enumerate(locals_):
+        if local_dtype == torch.bfloat16:
+            o1.append(oracle_mod.pseudograd_quantize(th, bf16_bits(l), off, local_is_bf16=True))
+        else:
+            o1.append(oracle_mod.pseudograd_quantize(th, t2n(l), off))
+    say(f"  oracle stage 1 x{W}: {time.time() - t0:.1f}s")
+    flips1 = 0
+    for p, l in enumerate(locals_):
+        c, lu, qp = B.pseudograd_quantize(theta, l, off)
+        torch.cuda.synchronize()
+        check_qparams(B.qparams_to_numpy(qp), o1[p][2])
+        flips1 += check_codes(t2n(c), o1[p][0], o1[p][3], off, o1[p][2])
+        check_luts(t2n(lu), o1[p][1], o1[p][0], off, o1[p][2])
+    pc = [torch.from_numpy(o[0]).to(DEV) for o in o1]
+    pl = [torch.from_numpy(o[1]).to(DEV) for o in o1]
+    acc_t = locals_[0].float() if materialise else None      # stored over (a copy of) theta_local
+    if materialise and local_dtype == torch.float32:
+        acc_t = locals_[0]
+    c2, l2, q2 = B.reduce_chunk(pc, pl, off, W, acc_out=acc_t)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[0] for o in o1], [o[1] for o in o1], off, W)
+    say(f"  oracle stage 2: {time.time() - t0:.1f}s")
+    check_qparams(B.qparams_to_numpy(q2), o_q2)
+    flips2 = check_codes(t2n(c2), o_c2, o_acc, off, o_q2)
+    check_luts(t2n(l2), o_l2, o_c2, off, o_q2)
+    if materialise:
+        assert np.array_equal(t2n(acc_t), o_acc)
+    mom = torch.zeros(n, dtype=torch.float32, device=DEV)
+    th_g = theta.clone()
+    B.outer_step(th_g, mom, LR, BETA, delta_codes=torch.from_numpy(o_c2).to(DEV),
+                 delta_lut=torch.from_numpy(o_l2).to(DEV), seg_offsets=off)
+    torch.cuda.synchronize()
+    th_o, m_o = th.copy(), np.zeros(n, dtype=np.float32)
+    oracle_mod.outer_step(th_o, m_o, LR, BETA, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=off)
+    check_outer(t2n(mom), m_o, np.zeros(n, dtype=np.float32), np.abs(m_o), "momentum")
+    check_outer(t2n(th_g), th_o, th, LR * (1 + BETA) * np.abs(m_o), "theta")
+    say(f"  N={n} T={len(sizes)} W={W}: stage-1 flips={flips1} stage-2 flips={flips2}")
+
+
+def test_config0_full(B, oracle_mod):
+    _full_chain(B, oracle_mod, synth.config_segment_sizes(0), synth.config_peers(0), "mixture")
+
+
+def test_config1_full_layer_w8(B, oracle_mod):
+    _full_chain(B, oracle_mod, synth.config_segment_sizes(1), synth.config_peers(1), "mixture")
+
+
+def _attention_block_sizes():
+    s = synth.layer_tensor_sizes()
+    return [s[0], s[1], s[2], s[3], s[7], s[8]]          # wq, wk, wv, wo and the two norm vectors
+
+
+def test_config3_structure_w14_heavy_tails_accumulate_over_theta_local(B, oracle_mod):
+    _full_chain(B, oracle_mod, _attention_block_sizes(), 14, "student_t3", materialise=True)
+
+
+def test_config4_structure_ring_chunks_bf16(B, oracle_mod):
+    """14 contiguous chunks (element count not divisible by 14: chunk starts are odd offsets),
+    each its own quantisation group; chunk owner adds its un-quantised fp32 data to 13 coded
+    contributions and divides by 14; theta_local arrives as bf16."""
+    sizes = _attention_block_sizes()
+    n = sum(sizes) + 5                                    # make it indivisible by 14
+    sizes = sizes + [5]
+    chunk_sizes = synth.ring_chunk_sizes(n, 14)
+    assert n % 14 != 0 and chunk_sizes[0] % 2 == 1
+    W = 13
+    theta, locals_, _ = synth.make_inputs([n], W + 1, device=DEV, local_dtype=torch.bfloat16)
+    th = t2n(theta)
+    chunk_off = synth.offsets_from_sizes(chunk_sizes)
+    # every peer quantises chunk by chunk (one group per chunk): oracle first
+    t0 = time.time()
+    o1 = [oracle_mod.pseudograd_quantize(th, bf16_bits(l), chunk_off, local_is_bf16=True) for l in locals_]
+    say(f"  oracle stage 1 x{W + 1} (bf16): {time.time() - t0:.1f}s")
+    g0 = B.pseudograd_quantize(theta, locals_[0], chunk_off)
+    torch.cuda.synchronize()
+    check_qparams(B.qparams_to_numpy(g0[2]), o1[0][2])
+    check_codes(t2n(g0[0]), o1[0][0], o1[0][3], chunk_off, o1[0][2])
+    check_luts(t2n(g0[1]), o1[0][1], o1[0][0], chunk_off, o1[0][2])
+    # the owner's own pseudo-gradient stays fp32 (peer index W), the other 13 arrive coded
+    local_fp32 = torch.from_numpy(o1[W][3]).to(DEV)
+    pcs = [torch.from_numpy(o[0]).to(DEV) for o in o1[:W]]
+    pls = [torch.from_numpy(o[1]).to(DEV) for o in o1[:W]]
+    codes_out = torch.empty(n, dtype=torch.uint8, device=DEV)
+    luts_out = torch.empty((14, 256), dtype=torch.float32, device=DEV)
+    ws = B.new_workspace(1, DEV)
+    total_flips = 0
+    for c in range(14):
+        a, b = chunk_off[c], chunk_off[c + 1]
+        loc_v = local_fp32[a:b]
+        c2, l2, q2 = B.reduce_chunk([pc[a:b] for pc in pcs], [pl[c:c + 1] for pl in pls], [0, b - a], 14,
+                                    local_fp32=loc_v, acc_out=loc_v, codes_out=codes_out[a:b],
+                                    lut_out=luts_out[c:c + 1], workspace=ws)
+        torch.cuda.synchronize()
+        o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce(
+            [np.ascontiguousarray(o[0][a:b]) for o in o1[:W]], [o[1][c:c + 1] for o in o1[:W]], [0, b - a], 14,
+            local_fp32=np.ascontiguousarray(o1[W][3][a:b]))
+        check_qparams(B.qparams_to_numpy(q2), o_q2)
+        total_flips += check_codes(t2n(c2), o_c2, o_acc, [0, b - a], o_q2)
+        check_luts(t2n(l2), o_l2, o_c2, [0, b - a], o_q2)
+        assert np.array_equal(t2n(loc_v), o_acc)
+    # outer step from the requantised chunks, new worker weights handed back as bf16
+    o_c2_all = t2n(codes_out)
+    o_l2_all = t2n(luts_out)
+    mom = torch.zeros(n, dtype=torch.float32, device=DEV)
+    th_g = theta.clone()
+    handback = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    B.outer_step(th_g, mom, LR, BETA, delta_codes=codes_out, delta_lut=luts_out, seg_offsets=chunk_off,
+                 theta_local_out=handback)
+    torch.cuda.synchronize()
+    th_o, m_o = th.copy(), np.zeros(n, dtype=np.float32)
+    oracle_mod.outer_step(th_o, m_o, LR, BETA, delta_codes=o_c2_all, delta_luts=o_l2_all, seg_offsets=chunk_off)
+    check_outer(t2n(th_g), th_o, th, LR * (1 + BETA) * np.abs(m_o), "theta")
+    assert torch.equal(handback, th_g.to(torch.bfloat16))
+    say(f"  14 chunks of {chunk_sizes[0]} (last {chunk_sizes[-1]}): flips={total_flips}")
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 2 at full size, in bench.py's launch configuration
+# ---------------------------------------------------------------------------------------------
+
+def test_config2_fullsize_sampled_tensors(B, oracle_mod):
+    sizes = synth.config_segment_sizes(2)
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 4
+    free, _ = torch.cuda.mem_get_info()
+    if free < 190e9:
+        pytest.skip(f"needs about 185 GB of free HBM, have {free / 1e9:.0f} GB")
+    # sampled tensors: final norm (4,096), layer 7 wk (4.2M), layer 41 wq (16.8M), layer 20 ffn_norm,
+    # layer 3 w_down (58.7M)
+    sample = [T - 2, 1 + 9 * 7 + 1, 1 + 9 * 41 + 0, 1 + 9 * 20 + 8, 1 + 9 * 3 + 6]
+    say(f"[config2] N={N} T={T}; sampled tensors {sample} sizes {[sizes[s] for s in sample]}")
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local = torch.empty(N, dtype=torch.float32, device=DEV)
+    mom = torch.zeros(N, dtype=torch.float32, device=DEV)
+    peer_codes = [torch.empty(N, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=DEV) for _ in range(W)]
+    qp = B.new_qparams(T, DEV)
+    ws = B.new_workspace(T, DEV)
+    th_s = {s: t2n(theta[off[s]:off[s + 1]]) for s in sample}
+    o1 = {s: [] for s in sample}
+    flips = 0
+    for p in list(range(1, W)) + [0]:
+        synth.fill_theta_local(local, theta, p, "mixture")
+        B.pseudograd_quantize(theta, local, off, codes_out=peer_codes[p], lut_out=peer_luts[p],
+                              qparams_out=qp, workspace=ws)
+        torch.cuda.synchronize()
+        g_qp = B.qparams_to_numpy(qp)
+        assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
+        for s in sample:
+            a, b = off[s], off[s + 1]
+            o = oracle_mod.pseudograd_quantize(th_s[s], t2n(local[a:b]), [0, b - a])
+            check_qparams(g_qp[s:s + 1], o[2])
+            flips += check_codes(t2n(peer_codes[p][a:b]), o[0], o[3], [0, b - a], o[2])
+            check_luts(t2n(peer_luts[p][s]), o[1], o[0], [0, b - a], o[2])
+            o1[s].append((p, o))
+            # hand the oracle's codes to the next stage (stage-isolated)
+            peer_codes[p][a:b].copy_(torch.from_numpy(o[0]))
+            peer_luts[p][s].copy_(torch.from_numpy(o[1][0]))
+        say(f"[config2] peer {p}: stage 1 checked on {len(sample)} tensors")
+    # any-size property on the largest tensor (embedding, 525M elements) of peer 0: the codebook
+    # is the bucket mean, so decoding preserves the tensor's sum
+    a, b = off[0], off[1]
+    d64 = (theta[a:b].double() - local[a:b].double())
+    dec = peer_luts[0][0][peer_codes[0][a:b].long()].double()
+    assert abs(float(dec.sum() - d64.sum())) <= 2 ** -22 * float(d64.abs().sum())
+    assert float((dec - d64).abs().max()) < 1.0                      # finite, no wild decode
+    del d64, dec
+    torch.cuda.empty_cache()
+
+    codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
+    lut2 = torch.empty((T, 256), dtype=torch.float32, device=DEV)
+    B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
+    torch.cuda.synchronize()
+    g_qp = B.qparams_to_numpy(qp)
+    assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
+    o2 = {}
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        by_peer = dict(o1[s])
+        o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([by_peer[p][0] for p in range(W)],
+                                                    [by_peer[p][1] for p in range(W)], [0, b - a], W)
+        check_qparams(g_qp[s:s + 1], o_q2)
+        flips += check_codes(t2n(codes2[a:b]), o_c2, o_acc, [0, b - a], o_q2)
+        check_luts(t2n(lut2[s]), o_l2, o_c2, [0, b - a], o_q2)
+        o2[s] = (o_c2, o_l2)
+        codes2[a:b].copy_(torch.from_numpy(o_c2))
+        lut2[s].copy_(torch.from_numpy(o_l2[0]))
+    say("[config2] stage 2 checked")
+    # requantisation keeps the sum of the fp32 average it encodes (any size): recompute the average
+    # of the embedding tensor with torch and compare sums
+    a, b = off[0], off[1]
+    acc = torch.zeros(b - a, dtype=torch.float32, device=DEV)
+    for p in range(W):
+        acc += peer_luts[p][0][peer_codes[p][a:b].long()]
+    acc *= 0.25
+    dec2 = lut2[0][codes2[a:b].long()]
+    assert abs(float(dec2.double().sum() - acc.double().sum())) <= 2 ** -22 * float(acc.double().abs().sum())
+    del acc, dec2
+    torch.cuda.empty_cache()
+
+    B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off, workspace=ws)
+    torch.cuda.synchronize()
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        th_o, m_o = th_s[s].copy(), np.zeros(b - a, dtype=np.float32)
+        oracle_mod.outer_step(th_o, m_o, LR, BETA, delta_codes=o2[s][0], delta_luts=o2[s][1], seg_offsets=[0, b - a])
+        check_outer(t2n(mom[a:b]), m_o, np.zeros(b - a, dtype=np.float32), np.abs(m_o), "momentum")
+        check_outer(t2n(theta[a:b]), th_o, th_s[s], LR * (1 + BETA) * np.abs(m_o), "theta")
+    # first step from a zero buffer: m' = g everywhere, theta moved by lr (1 + beta) g (any size)
+    a, b = off[0], off[1]
+    g = lut2[0][codes2[a:b].long()]
+    assert torch.equal(mom[a:b], g)
+    say(f"[config2] stage 3 checked; total one-bucket flips on sampled tensors: {flips}")
