@@ -51,8 +51,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 fp32 (1 GiB read, 1 GiB written) so that "
                          "profiler byte counters can be scaled against a kernel of known traffic")
-    ap.add_argument("--traffic-kib", type=float, default=None,
-                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (optional)")
+    ap.add_argument("--cpu-layers", type=int, default=4,
+                    help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (peers are int8 buffers in local HBM); "
@@ -103,8 +103,7 @@ def main():
     # ---- CPU oracle on a bounded sample, before theta is modified (baseline only) -------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
-        cpu_baseline = cpu_oracle_baseline(np, torch, synth, theta, local, peer_codes, peer_luts, off, sizes,
-                                           cfg, W)
+        cpu_baseline = cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, args.cpu_layers)
 
     def step(events=None):
         if events is not None:
@@ -190,9 +189,7 @@ def main():
         log(f"[bench] {s}: {avg:.3f} ms  {stages[s]['GB/s']:.1f} GB/s ({100 * stages[s]['GB/s'] / HBM_PEAK_GBS:.1f}%)")
     dominant = max(names, key=lambda n: kernels[n]["avg_ms"])
     achieved = kernels[dominant]["GB/s"]
-    traffic = None
-    if args.traffic_kib is not None:
-        traffic = args.traffic_kib * 1024.0
+    traffic = measured_traffic_bytes(dominant) if cfg == 2 else None
     result = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
@@ -211,14 +208,32 @@ def main():
     print(json.dumps(result), flush=True)
 
 
-def cpu_oracle_baseline(np, torch, synth, theta, local, peer_codes, peer_luts, off, sizes, cfg, W):
-    """Times the oracle's three stages on the first decoder layer's tensors of the same workload
-    (218,112,000 elements, 9 tensors), copied down from the device."""
+def measured_traffic_bytes(kernel_name):
+    """HBM bytes per launch of `kernel_name` from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic_config2.txt: FETCH_SIZE and WRITE_SIZE in KiB per dispatch and the factors
+    that a plain copy of known size gave for the same counters).  None if the file or the row is
+    missing: the figure is measured offline, never estimated here."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_config2.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("#") or "|" not in line:
+            continue
+        cols = [c.strip() for c in line.split("|")]
+        if cols[0] == kernel_name and len(cols) >= 5:
+            fetch_kib, write_kib, fetch_factor, write_factor = (float(c) for c in cols[1:5])
+            return round((fetch_kib / fetch_factor + write_kib / write_factor) * 1024.0)
+    return None
+
+
+def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, layers):
+    """Times the oracle's three stages on the first decoder layers of the same workload
+    (9 tensors, 218,112,000 elements per layer), copied down from the device."""
     import oracle
     from oracle import build as obuild
     obuild.build(force=False)
     if cfg == 2:
-        first, last = 1, 10             # tensors 1..9 = layer 0 (tensor 0 is the embedding)
+        first, last = 1, 1 + 9 * max(1, layers)      # tensor 0 is the embedding
     else:
         first, last = 0, min(len(sizes), 9)
     a, b = off[first], off[last]
@@ -226,14 +241,13 @@ def cpu_oracle_baseline(np, torch, synth, theta, local, peer_codes, peer_luts, o
     n = b - a
     th = theta[a:b].cpu().numpy()
     lo = local[a:b].cpu().numpy()
-    # contributions of the other peers: the GPU's own codes are NOT used; the oracle makes its own
-    # from freshly generated theta_local slices (setup, untimed)
+    # contributions of the other peers: the oracle makes its own codes from freshly generated
+    # theta_local slices (setup, untimed); nothing the GPU library produced is used
     pcs, pls = [], []
     scratch = torch.empty(n, dtype=torch.float32, device=theta.device)
     threads = oracle.num_threads()
     t_setup = time.perf_counter()
     for p in range(1, W):
-        # same generator stream layout as the full-size fill is not needed here: any seeded peer will do
         synth.fill_theta_local(scratch, theta[a:b], p, synth.config_delta_kind(cfg), seed=synth.BASE_SEED + 1)
         c, l, _, _ = oracle.pseudograd_quantize(th, scratch.cpu().numpy(), sample_off)
         pcs.append(c)
@@ -251,11 +265,14 @@ def cpu_oracle_baseline(np, torch, synth, theta, local, peer_codes, peer_luts, o
     oracle.outer_step(th2, m, LR, BETA, delta_codes=c2, delta_luts=l2, seg_offsets=sample_off)
     t5 = time.perf_counter()
     secs = (t2 - t1) + (t3 - t2) + (t5 - t4)
-    gbs = (17 + 2 * W + 1 + 17) * n / secs / 1e9
+    bpe = 17 + 2 * W + 1 + 17
+    gbs = bpe * n / secs / 1e9
     log(f"[bench] cpu baseline: stage1 {t2 - t1:.2f}s stage2 {t3 - t2:.2f}s stage3 {t5 - t4:.2f}s -> {gbs:.2f} GB/s")
     return {"value": round(gbs, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": f"first decoder layer's 9 tensors of the same workload ({n} elements, W={W}), "
-                      f"same {17 + 2 * W + 1 + 17} B/element accounting; stage seconds: {t2 - t1:.2f}/{t3 - t2:.2f}/{t5 - t4:.2f}",
+            "sample": f"first {max(1, layers) if cfg == 2 else 1} decoder layer(s) of the same workload "
+                      f"({n} elements in {len(sample_off) - 1} tensors, W={W}), same {bpe} B/element "
+                      f"accounting; wall seconds per stage: {t2 - t1:.2f}/{t3 - t2:.2f}/{t5 - t4:.2f} "
+                      f"(about {secs * threads:.0f} core-seconds)",
             "seconds": round(secs, 3)}
 
 
