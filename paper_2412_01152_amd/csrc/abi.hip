@@ -79,6 +79,7 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     p.hcnt = (unsigned long long*)(ws + L.hcnt);
     p.osum = (double*)(ws + L.osum);
     p.ocnt = (unsigned long long*)(ws + L.ocnt);
+    p.counters = (unsigned long long*)(ws + L.counters);
     p.stream = stream;
     int32_t rc = num_compute_units(&p.num_cus);
     if (rc) return rc;
@@ -110,10 +111,10 @@ hipError_t run_stats(const Src& src, const Pass& p) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, false>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
-                       g.per_block, p.stats, p.pivot, (float*)nullptr);
+                       g.work, p.stats, p.pivot, (float*)nullptr);
     e = hipGetLastError();
     (void)mark(1, p.stream);
     return e;
@@ -122,10 +123,10 @@ hipError_t run_stats(const Src& src, const Pass& p) {
 template <class Src>
 hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     constexpr auto kernel = quant_kernel<Src, DILOCO_COPIES_STREAM>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1);
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
-                       g.per_block, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
+                       g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
@@ -162,14 +163,14 @@ hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t
     (void)mark(0, stream);
     if (delta) {
         constexpr auto kernel = outer_fp32_kernel<kOut>;
-        Grid g = plan_grid(N, num_cus, resident_blocks_per_cu<kernel>());
+        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>());
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, delta, N,
-                           g.per_block, lr, beta, local_out);
+                           g.work, lr, beta, local_out);
     } else {
         constexpr auto kernel = outer_coded_kernel<kOut>;
-        Grid g = plan_grid(N, num_cus, resident_blocks_per_cu<kernel>());
+        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>());
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, codes, lut, seg, T,
-                           N, g.per_block, lr, beta, local_out);
+                           N, g.work, lr, beta, local_out);
     }
     hipError_t e = hipGetLastError();
     (void)mark(1, stream);

@@ -102,18 +102,44 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     return (uint16_t)(b >> 16);
 }
 
-// The flat buffer [0, N) is cut into equal contiguous shares, one per block; a share is a
-// multiple of kIter so that full iterations start on the same phase in every block.
+// Work distribution of the streaming passes.  The flat buffer [0, N) is cut into chunks of
+// `chunk` elements (a multiple of kIter); the resident blocks claim chunks in address order from a
+// global counter until none is left.  Blocks of one launch progress at very different speeds on
+// this chip (measured: up to 2.7x apart in a static partition, so the slowest blocks ran alone
+// for a third of the kernel), which a static split turns into idle compute units; claiming keeps
+// every block busy to the end.  The next claim is issued before the current chunk is processed,
+// so its latency is hidden.  Every wave leaves the loop when the counter passes num_chunks.
+struct Work {
+    unsigned long long* counter;   // device, zero before the launch; nullptr: chunks are dealt
+                                   // round-robin (block b takes b, b + grid, ...) without a counter
+    uint64_t chunk;                // elements per claim
+    uint64_t num_chunks;
+};
 struct Share {
     uint64_t begin, end;
 };
-__device__ __forceinline__ Share block_share(uint64_t N, uint64_t per_block) {
-    Share r;
-    r.begin = (uint64_t)blockIdx.x * per_block;
-    uint64_t e = r.begin + per_block;
-    r.end = e < N ? e : N;
-    return r;
-}
+struct Claimer {
+    unsigned long long next;
+    __device__ __forceinline__ explicit Claimer(const Work& w) : next(blockIdx.x) {
+        if (w.counter && threadIdx.x == 0) next = atomicAdd(w.counter, 1ull);
+    }
+    // Block-uniform.  `slot` is one 64-bit word of LDS.
+    __device__ __forceinline__ bool claim(const Work& w, uint64_t N, Share& sh, unsigned long long* slot) {
+        if (threadIdx.x == 0) *slot = next;
+        __syncthreads();
+        const unsigned long long c = *slot;
+        __syncthreads();
+        if (c >= w.num_chunks) return false;
+        if (!w.counter)
+            next += gridDim.x;
+        else if (threadIdx.x == 0)
+            next = atomicAdd(w.counter, 1ull);
+        sh.begin = c * w.chunk;
+        const uint64_t e = sh.begin + w.chunk;
+        sh.end = e < N ? e : N;
+        return true;
+    }
+};
 
 // Index of the segment that holds element `pos` (pos < seg[T]): the smallest s with seg[s+1] > pos.
 __device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg, uint32_t T,
@@ -178,8 +204,9 @@ __device__ __forceinline__ float offset_scale(float inv_w) {
 
 // Device scratch layout (all offsets in bytes from a 256-byte aligned base).
 struct WorkspaceLayout {
-    size_t seg, stats, pivot, hsumq, hcnt, osum, ocnt, total;
+    size_t seg, stats, pivot, hsumq, hcnt, osum, ocnt, counters, total;
 };
+constexpr int kNumCounters = 4;     // chunk counters: pass A, pass B, outer step, spare
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 __host__ inline WorkspaceLayout workspace_layout(uint32_t T) {
     WorkspaceLayout L;
@@ -198,6 +225,8 @@ __host__ inline WorkspaceLayout workspace_layout(uint32_t T) {
     o = align_up(o + sizeof(double) * 2 * (size_t)T, 256);
     L.ocnt = o;
     o = align_up(o + sizeof(unsigned long long) * 2 * (size_t)T, 256);
+    L.counters = o;
+    o = align_up(o + sizeof(unsigned long long) * kNumCounters, 256);
     L.total = o;
     return L;
 }

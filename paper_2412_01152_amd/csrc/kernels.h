@@ -156,17 +156,19 @@ __global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t
 
 template <class Src, bool kWriteAcc>
 __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src src_in, const uint64_t* __restrict__ seg,
-                                                        uint32_t T, uint64_t N, uint64_t per_block,
+                                                        uint32_t T, uint64_t N, Work work,
                                                         double* __restrict__ stats,
                                                         const float* __restrict__ pivot,
                                                         float* acc_out) {
     __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
     __shared__ double s_red[8];
+    __shared__ unsigned long long s_claim;
     Src src = src_in;
     src.bind(s_src);
-    const Share sh = block_share(N, per_block);
-    if (sh.begin >= sh.end) return;
     const int tid = threadIdx.x;
+    Claimer claimer(work);
+    Share sh;
+    while (claimer.claim(work, N, sh, &s_claim)) {
     uint32_t s = find_segment(seg, T, sh.begin);
     uint64_t pos = sh.begin;
     while (pos < sh.end) {
@@ -210,6 +212,7 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src s
             atomicAdd(&stats[2 * (size_t)s + 1], s2);
         }
         pos = sub_end;
+    }
     }
 }
 
@@ -311,18 +314,20 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
 // (a 64-bit bin spans two of the 32 banks; with 16 copies 16 consecutive lanes never collide).
 template <class Src, int kCopies>
 __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
-                                                        uint32_t T, uint64_t N, uint64_t per_block,
+                                                        uint32_t T, uint64_t N, Work work,
                                                         const diloco_qparams* __restrict__ qp,
                                                         uint8_t* __restrict__ codes, PassBOut out) {
     __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
     __shared__ unsigned long long s_bin_all[kBuckets * kCopies];
     __shared__ double s_red[8];
+    __shared__ unsigned long long s_claim;
     Src src = src_in;
     src.bind(s_src);
-    const Share sh = block_share(N, per_block);
-    if (sh.begin >= sh.end) return;
     const int tid = threadIdx.x;
     unsigned long long* const s_bin = s_bin_all + (tid & (kCopies - 1));   // this lane's copy
+    Claimer claimer(work);
+    Share sh;
+    while (claimer.claim(work, N, sh, &s_claim)) {
     uint32_t s = find_segment(seg, T, sh.begin);
     uint64_t pos = sh.begin;
     while (pos < sh.end) {
@@ -397,6 +402,7 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src s
             }
         }
         pos = sub_end;
+    }
     }
 }
 

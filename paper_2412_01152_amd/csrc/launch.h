@@ -19,6 +19,7 @@ struct Pass {
     unsigned long long* hcnt;   // device, [T][256]
     double* osum;               // device, [T][2]
     unsigned long long* ocnt;   // device, [T][2]
+    unsigned long long* counters;   // device, [kNumCounters], zero at the start of the call
     int num_cus;
     hipStream_t stream;
 };
@@ -56,21 +57,29 @@ inline int resident_blocks_per_cu() {
     return occ;
 }
 
-// One contiguous share of the flat buffer per block, all blocks resident at once: grid = CUs x
-// resident blocks (fewer when the buffer is small), share rounded up to whole iterations.
+// Launch shape of a streaming pass: all blocks resident (grid = CUs x resident blocks, fewer when
+// the buffer is small), chunks of at most 32 block iterations claimed dynamically, at least about
+// 16 chunks per block when the buffer is small so that the claiming can still balance the load.
 struct Grid {
     uint32_t blocks;
-    uint64_t per_block;
+    Work work;
 };
-inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu) {
+#ifndef DILOCO_CHUNK_ITERS
+#define DILOCO_CHUNK_ITERS 32
+#endif
+constexpr uint64_t kMaxChunkIters = DILOCO_CHUNK_ITERS;
+inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long long* counter) {
     Grid g;
-    uint64_t want = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
+    const uint64_t resident = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
     uint64_t iters = (N + kIter - 1) / kIter;
     if (iters < 1) iters = 1;
-    if (want > iters) want = iters;
-    uint64_t iters_per_block = (iters + want - 1) / want;
-    g.per_block = iters_per_block * kIter;
-    g.blocks = (uint32_t)((N + g.per_block - 1) / g.per_block);
+    uint64_t chunk_iters = iters / (resident * 16);
+    if (chunk_iters < 1) chunk_iters = 1;
+    if (chunk_iters > kMaxChunkIters) chunk_iters = kMaxChunkIters;
+    g.work.counter = counter;
+    g.work.chunk = chunk_iters * kIter;
+    g.work.num_chunks = (N + g.work.chunk - 1) / g.work.chunk;
+    g.blocks = (uint32_t)(g.work.num_chunks < resident ? g.work.num_chunks : resident);
     if (g.blocks < 1) g.blocks = 1;
     return g;
 }
@@ -86,6 +95,22 @@ DILOCO_DECLARE_REDUCE_GROUP(1)
 DILOCO_DECLARE_REDUCE_GROUP(2)
 DILOCO_DECLARE_REDUCE_GROUP(3)
 #undef DILOCO_DECLARE_REDUCE_GROUP
+
+// One contiguous share per block, no counter: the in-place outer step runs fastest as long walks
+// (measured: 28 ms with one share per block or 2M-element chunks, 32 ms with 128K-element chunks).
+inline Grid plan_static(uint64_t N, int num_cus, int blocks_per_cu) {
+    Grid g;
+    uint64_t want = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
+    uint64_t iters = (N + kIter - 1) / kIter;
+    if (iters < 1) iters = 1;
+    if (want > iters) want = iters;
+    g.work.counter = nullptr;
+    g.work.chunk = (iters + want - 1) / want * kIter;
+    g.work.num_chunks = (N + g.work.chunk - 1) / g.work.chunk;
+    g.blocks = (uint32_t)g.work.num_chunks;
+    if (g.blocks < 1) g.blocks = 1;
+    return g;
+}
 
 inline int reduce_group_of(uint32_t W) { return W <= 4 ? 0 : (W <= 8 ? 1 : (W <= 12 ? 2 : 3)); }
 

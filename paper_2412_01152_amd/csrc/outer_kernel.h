@@ -45,11 +45,13 @@ __device__ __forceinline__ void nesterov1(float* theta, float* mom, void* local_
 template <int kOut>
 __global__ __launch_bounds__(kThreads) void outer_fp32_kernel(float* theta, float* mom,
                                                              const float* __restrict__ delta,
-                                                             uint64_t N, uint64_t per_block, float lr,
+                                                             uint64_t N, Work work, float lr,
                                                              float beta, void* local_out) {
-    const Share sh = block_share(N, per_block);
-    if (sh.begin >= sh.end) return;
+    __shared__ unsigned long long s_claim;
     const int tid = threadIdx.x;
+    Claimer claimer(work);
+    Share sh;
+    while (claimer.claim(work, N, sh, &s_claim)) {
     uint64_t base = sh.begin;
     for (; base + kIter <= sh.end; base += kIter) {
         f32x4 g[kUnroll], m[kUnroll], th[kUnroll];
@@ -67,6 +69,7 @@ __global__ __launch_bounds__(kThreads) void outer_fp32_kernel(float* theta, floa
     }
     for (uint64_t i = base + tid; i < sh.end; i += kThreads)
         nesterov1<kOut>(theta, mom, local_out, i, delta[i], lr, beta);
+    }
 }
 
 template <int kOut>
@@ -75,12 +78,14 @@ __global__ __launch_bounds__(kThreads) void outer_coded_kernel(float* theta, flo
                                                               const float* __restrict__ lut,
                                                               const uint64_t* __restrict__ seg,
                                                               uint32_t T, uint64_t N,
-                                                              uint64_t per_block, float lr, float beta,
+                                                              Work work, float lr, float beta,
                                                               void* local_out) {
     __shared__ float s_lut[kBuckets];
-    const Share sh = block_share(N, per_block);
-    if (sh.begin >= sh.end) return;
+    __shared__ unsigned long long s_claim;
     const int tid = threadIdx.x;
+    Claimer claimer(work);
+    Share sh;
+    while (claimer.claim(work, N, sh, &s_claim)) {
     uint32_t s = find_segment(seg, T, sh.begin);
     uint64_t pos = sh.begin;
     while (pos < sh.end) {
@@ -116,6 +121,7 @@ __global__ __launch_bounds__(kThreads) void outer_coded_kernel(float* theta, flo
         for (uint64_t i = base + tid; i < sub_end; i += kThreads)
             nesterov1<kOut>(theta, mom, local_out, i, s_lut[codes[i]], lr, beta);
         pos = sub_end;
+    }
     }
 }
 

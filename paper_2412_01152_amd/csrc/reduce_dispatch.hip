@@ -33,10 +33,10 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, kWriteAcc>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
-                       p.T, p.N, g.per_block, p.stats, p.pivot, acc_out);
+                       p.T, p.N, g.work, p.stats, p.pivot, acc_out);
     e = hipGetLastError();
     (void)mark(1, p.stream);
     return e;
@@ -46,10 +46,10 @@ template <int W, bool kLocal, bool kTrueDiv>
 hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
     constexpr auto kernel = quant_kernel<Src, DILOCO_COPIES_REDUCE>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>());
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1);
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
-                       p.T, p.N, g.per_block, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
+                       p.T, p.N, g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
