@@ -175,6 +175,8 @@ def main():
         stage_ms["stage1"].append(s1[0].elapsed_time(s1[3]))
         stage_ms["stage2"].append(s2[0].elapsed_time(s2[3]))
         stage_ms["stage3"].append(s3[0].elapsed_time(s3[1]))
+    for k in range(args.steps):
+        log("[bench] step %2d: " % k + "  ".join(f"{dur[n][k]:7.3f}" for n in names) + "  ms")
     kernels = {}
     for n in names:
         avg = float(np.mean(dur[n]))
