@@ -46,11 +46,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration (0, 1 or 2)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration: 2 (default, the graded workload); 0 and 1 are the small cases; "
+                         "3 times the reduce step alone at W = 14")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 fp32 (1 GiB read, 1 GiB written) so that "
                          "profiler byte counters can be scaled against a kernel of known traffic")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the timed steps also time the other variants of the three calls on the same "
+                         "resident data (bf16 theta_local, stored accumulation, fp32 delta, hand-back)")
+    ap.add_argument("--aligned-chunks", action="store_true",
+                    help="config 4 only: round the ring chunk up to a multiple of 1024 elements")
     ap.add_argument("--cpu-layers", type=int, default=4,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
@@ -71,6 +77,10 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = args.config
+    if cfg == 3:
+        return bench_config3(args, np, torch, B, synth, dev)
+    if cfg == 4:
+        return bench_config4(args, np, torch, B, synth, dev)
     sizes = synth.config_segment_sizes(cfg)
     off = synth.offsets_from_sizes(sizes)
     N, T = off[-1], len(sizes)
@@ -189,6 +199,10 @@ def main():
         avg = float(np.mean(v))
         stages[s] = {"avg_ms": round(avg, 4), "GB/s": round(STAGE_BYTES[s] * N / (avg * 1e-3) / 1e9, 1)}
         log(f"[bench] {s}: {avg:.3f} ms  {stages[s]['GB/s']:.1f} GB/s ({100 * stages[s]['GB/s'] / HBM_PEAK_GBS:.1f}%)")
+    extras = None
+    if args.extras:
+        extras = time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws,
+                             off, N, T, W)
     dominant = max(names, key=lambda n: kernels[n]["avg_ms"])
     achieved = kernels[dominant]["GB/s"]
     traffic = measured_traffic_bytes(dominant) if cfg == 2 else None
@@ -204,10 +218,194 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": KERNEL_BYTES[dominant] * N},
-        "kernels": kernels, "stages": stages,
+        "kernels": kernels, "stages": stages, "extras": extras,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(result), flush=True)
+
+
+def bench_config3(args, np, torch, B, synth, dev):
+    """Configuration 3: the reduce step alone at W = 14 heavy-tailed coded peers on the full 10B set
+    (143 GB of codes resident), accumulation stored over theta_local (no room for a fourth fp32 array
+    next to theta_outer, theta_local and momentum in the real layout)."""
+    sizes = synth.config_segment_sizes(3)
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 14
+    log(f"[bench] config 3: N={N} T={T} W={W}; allocating {(W + 1) * N / 1e9 + 8 * N / 1e9:.0f} GB")
+    t0 = time.time()
+    theta = torch.empty(N, dtype=torch.float32, device=dev)
+    local = torch.empty(N, dtype=torch.float32, device=dev)
+    peer_codes = [torch.empty(N, dtype=torch.uint8, device=dev) for _ in range(W)]
+    peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=dev) for _ in range(W)]
+    codes2 = torch.empty(N, dtype=torch.uint8, device=dev)
+    lut2 = torch.empty((T, 256), dtype=torch.float32, device=dev)
+    qp = B.new_qparams(T, dev)
+    ws = B.new_workspace(T, dev)
+    synth.fill_theta_outer(theta)
+    for p in range(W):
+        synth.fill_theta_local(local, theta, p, "student_t3")
+        B.pseudograd_quantize(theta, local, off, codes_out=peer_codes[p], lut_out=peer_luts[p], qparams_out=qp,
+                              workspace=ws)
+    torch.cuda.synchronize()
+    log(f"[bench] {W} peers ready ({time.time() - t0:.1f}s)")
+
+    def step(events=None):
+        if events is not None:
+            B.profile_passes(events)
+        B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=local, codes_out=codes2, lut_out=lut2,
+                       qparams_out=qp, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = []
+    for _ in range(args.steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for x in e:
+            x.record()
+        evs.append(e)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step([x.cuda_event for x in evs[k]])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    B.profile_passes(None)
+    a_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    b_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    bpe = W + 9
+    value = bpe * N / (elapsed / args.steps) / 1e9
+    kernels = {f"stage2_stats(reduce W={W}, store acc)": {"avg_ms": round(a_ms, 3), "GB/s": round((W + 4) * N / a_ms / 1e6, 1)},
+               "stage2_quant(stored acc)": {"avg_ms": round(b_ms, 3), "GB/s": round(5 * N / b_ms / 1e6, 1)}}
+    for k, v in kernels.items():
+        log(f"[bench] {k:40s} avg {v['avg_ms']:8.3f} ms  {v['GB/s']:8.1f} GB/s  {100 * v['GB/s'] / HBM_PEAK_GBS:.1f}% of peak")
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    result = {"metric": "int8 reduce W=14 (stored accumulation): GB/s & % HBM peak, 10B", "value": round(value, 1),
+              "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": round(elapsed * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "config": {"workload": f"config3: 10B-shaped parameter set, {N} elements in {T} tensors, W=14 coded "
+                                     f"peers (Student-t nu=3 deltas), int8_reduce_chunk only", "elements": N,
+                         "segments": T, "peers": W, "bytes_per_element_per_step": bpe},
+              "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+              "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GB/s"], "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": round(kernels[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": None},
+              "kernels": kernels, "cpu_baseline": None}
+    print(json.dumps(result), flush=True)
+
+
+def bench_config4(args, np, torch, B, synth, dev):
+    """Configuration 4: ring granularity.  The 10B set is cut into 14 contiguous chunks of
+    ceil(N / 14) = 729,384,375 elements (odd: every other chunk starts on a 4-byte boundary only);
+    int8_reduce_chunk runs once per chunk on 13 coded contributions plus the owner's fp32 data
+    (stored in place), each chunk its own quantisation group.  One step = the 14 calls."""
+    N = synth.n_elements(2)
+    chunk_sizes = synth.ring_chunk_sizes(N, 14)
+    if args.aligned_chunks:                       # chunk rounded up to a multiple of 1024 elements
+        c = -(-chunk_sizes[0] // 1024) * 1024
+        chunk_sizes = [c] * 13 + [N - 13 * c]
+    coff = synth.offsets_from_sizes(chunk_sizes)
+    W = 13
+    log(f"[bench] config 4: N={N}, 14 chunks of {chunk_sizes[0]} (last {chunk_sizes[-1]}), W={W} coded + local")
+    t0 = time.time()
+    theta = torch.empty(N, dtype=torch.float32, device=dev)
+    local = torch.empty(N, dtype=torch.float32, device=dev)
+    peer_codes = [torch.empty(N, dtype=torch.uint8, device=dev) for _ in range(W)]
+    peer_luts = [torch.empty((14, 256), dtype=torch.float32, device=dev) for _ in range(W)]
+    codes2 = torch.empty(N, dtype=torch.uint8, device=dev)
+    lut2 = torch.empty((14, 256), dtype=torch.float32, device=dev)
+    qp = B.new_qparams(14, dev)
+    ws = B.new_workspace(14, dev)
+    synth.fill_theta_outer(theta)
+    for p in range(W):
+        synth.fill_theta_local(local, theta, p, "mixture")
+        B.pseudograd_quantize(theta, local, coff, codes_out=peer_codes[p], lut_out=peer_luts[p], qparams_out=qp,
+                              workspace=ws)
+    synth.fill_theta_local(local, theta, W, "mixture")
+    local.sub_(theta).neg_()                      # the owner's own fp32 pseudo-gradient (input preparation)
+    torch.cuda.synchronize()
+    del theta
+    log(f"[bench] {W} peers ready ({time.time() - t0:.1f}s)")
+    qp1 = B.new_qparams(1, dev)
+
+    def step():
+        for c in range(14):
+            a, b = coff[c], coff[c + 1]
+            B.reduce_chunk([pc[a:b] for pc in peer_codes], [pl[c:c + 1] for pl in peer_luts], [0, b - a], 14,
+                           local_fp32=local[a:b], acc_out=local[a:b], codes_out=codes2[a:b],
+                           lut_out=lut2[c:c + 1], qparams_out=qp1, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    bpe = W + 13
+    value = bpe * N / (elapsed / args.steps) / 1e9
+    log(f"[bench] 14 chunk calls: {elapsed * 1e3 / args.steps:.3f} ms  {value:.1f} GB/s ({100 * value / HBM_PEAK_GBS:.1f}% of peak)")
+    result = {"metric": "int8 reduce per ring chunk, 13 coded + fp32 local: GB/s & % HBM peak, 10B",
+              "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": round(elapsed * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "config": {"workload": f"config4: {N} elements as 14 ring chunks of {chunk_sizes[0]}, 13 coded peers + "
+                                     f"fp32 local, divisor 14, one int8_reduce_chunk call per chunk",
+                         "elements": N, "segments": 14, "peers": W, "bytes_per_element_per_step": bpe},
+              "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "roofline": None, "cpu_baseline": None}
+    print(json.dumps(result), flush=True)
+
+
+def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws, off, N, T, W):
+    """Whole-call timings (HIP events around the call, 5 repetitions) of the variants bench's step does
+    not use.  Runs last: the stored-accumulation variant overwrites theta_local."""
+    out = {}
+
+    def timed(name, bytes_per_elem, fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbs = bytes_per_elem * N / (ms * 1e-3) / 1e9
+        out[name] = {"ms": round(ms, 3), "bytes_per_element": bytes_per_elem, "GB/s": round(gbs, 1),
+                     "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        log(f"[bench] extra {name:52s} {ms:8.3f} ms  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:.1f}% of peak")
+
+    local_bf16 = local.to(torch.bfloat16)
+    timed("stage1 bf16 theta_local (13 B/elem)", 13,
+          lambda: B.pseudograd_quantize(theta, local_bf16, off, codes_out=codes1, lut_out=lut1, qparams_out=qp,
+                                        workspace=ws))
+    timed("stage3 coded + bf16 hand-back (19 B/elem)", 19,
+          lambda: B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off,
+                               theta_local_out=local_bf16, workspace=ws))
+    del local_bf16
+    timed(f"stage2 W={W} storing the accumulation ({W + 9} B/elem)", W + 9,
+          lambda: B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=local, codes_out=codes2, lut_out=lut2,
+                                 qparams_out=qp, workspace=ws))
+    timed(f"stage2 W={W - 1} + fp32 local, in place ({W - 1 + 13} B/elem)", W - 1 + 13,
+          lambda: B.reduce_chunk(peer_codes[1:], peer_luts[1:], off, W, local_fp32=local, acc_out=local,
+                                 codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws))
+    timed("stage3 fp32 delta (20 B/elem)", 20,
+          lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local))
+    timed("stage3 fp32 delta + fp32 hand-back (24 B/elem)", 24,
+          lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local, theta_local_out=codes_as_f32(torch, codes1, codes2, N)))
+    return out
+
+
+def codes_as_f32(torch, codes1, codes2, N):
+    """A throw-away fp32 [N] destination for the hand-back timing, if one fits in free memory."""
+    global _SCRATCH_F32
+    try:
+        return _SCRATCH_F32
+    except NameError:
+        _SCRATCH_F32 = torch.empty(N, dtype=torch.float32, device=codes1.device)
+        return _SCRATCH_F32
 
 
 def measured_traffic_bytes(kernel_name):

@@ -105,13 +105,13 @@ hipError_t finalize_lut(const Pass& p, const diloco_qparams* qp, float* lut) {
 }
 
 template <class Src>
-hipError_t run_stats(const Src& src, const Pass& p) {
+hipError_t run_stats(const Src& src, const Pass& p, uint32_t phase) {
     hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + 255) / 256), dim3(256), 0, p.stream, src, p.seg, p.T,
                        p.pivot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, false>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0);
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0, phase);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
                        g.work, p.stats, p.pivot, (float*)nullptr);
@@ -123,7 +123,7 @@ hipError_t run_stats(const Src& src, const Pass& p) {
 template <class Src>
 hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     constexpr auto kernel = quant_kernel<Src, DILOCO_COPIES_STREAM>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1);
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1));
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
                        g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
@@ -163,12 +163,12 @@ hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t
     (void)mark(0, stream);
     if (delta) {
         constexpr auto kernel = outer_fp32_kernel<kOut>;
-        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>());
+        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>(), host_phase(theta, 4));
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, delta, N,
                            g.work, lr, beta, local_out);
     } else {
         constexpr auto kernel = outer_coded_kernel<kOut>;
-        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>());
+        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>(), host_phase(theta, 4));
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, codes, lut, seg, T,
                            N, g.work, lr, beta, local_out);
     }
@@ -224,12 +224,12 @@ int32_t diloco_pseudograd_quantize(const float* theta_outer, const void* theta_l
     if (rc) return rc;
     if (local_dtype == DILOCO_DTYPE_BF16) {
         SrcPseudoGrad<true> src{theta_outer, theta_local};
-        if (N) DILOCO_TRY(run_stats(src, p));
+        if (N) DILOCO_TRY(run_stats(src, p, host_phase(theta_outer, 4)));
         DILOCO_TRY(finalize_qparams(p, qparams_out));
         if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
     } else {
         SrcPseudoGrad<false> src{theta_outer, theta_local};
-        if (N) DILOCO_TRY(run_stats(src, p));
+        if (N) DILOCO_TRY(run_stats(src, p, host_phase(theta_outer, 4)));
         DILOCO_TRY(finalize_qparams(p, qparams_out));
         if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
     }

@@ -34,7 +34,8 @@ constexpr int kOffsetBias = 1 << 22;
 constexpr float kRoundMagic = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer
 constexpr int kCountShift = 40;
 constexpr int kFlushIters = 16;                     // 16 * kIter = 2^16 elements between drains
-static_assert((long long)(kFlushIters + 1) * kIter * (1ll << 23) <= (1ll << kCountShift), "bin overflow");
+// between two drains: kFlushIters iterations, one ragged tail (< kIter) and one head (< 128)
+static_assert((long long)(kFlushIters + 2) * kIter * (1ll << 23) <= (1ll << kCountShift), "bin overflow");
 
 // Vector types that promise only element alignment: gfx950 global memory instructions accept
 // any byte address, so one dwordx4 / dwordx2 / dword access is emitted whatever the pointer's
@@ -114,6 +115,9 @@ struct Work {
                                    // round-robin (block b takes b, b + grid, ...) without a counter
     uint64_t chunk;                // elements per claim
     uint64_t num_chunks;
+    uint32_t phase;                // reference stream's address in elements, modulo kAlignElems
+    uint32_t origin;               // (kAlignElems - phase) % kAlignElems: chunk c >= 1 starts at
+                                   // origin + c * chunk, a line-aligned position; chunk 0 at element 0
 };
 struct Share {
     uint64_t begin, end;
@@ -134,12 +138,28 @@ struct Claimer {
             next += gridDim.x;
         else if (threadIdx.x == 0)
             next = atomicAdd(w.counter, 1ull);
-        sh.begin = c * w.chunk;
-        const uint64_t e = sh.begin + w.chunk;
+        sh.begin = c ? w.origin + c * w.chunk : 0;
+        const uint64_t e = w.origin + (c + 1) * w.chunk;
         sh.end = e < N ? e : N;
         return true;
     }
 };
+
+// Pointers need only element alignment, but the streaming loops run about a fifth faster when a
+// wave's accesses start on 128-byte lines (measured: views shifted by 1, 3, 5 or 16 elements all
+// cost the same 15-20 %, so it is the cache-line straddling and the partial-line writes that hurt,
+// not the width of the vector access).  Each piece of work therefore starts with up to 127 single
+// elements, until element index + phase is a multiple of 128, where phase is the reference
+// stream's address in elements modulo 128 (taken by the host from the pointer it passes; chunk
+// starts are shifted to the same phase).  Streams that share the reference's phase (views of
+// line-aligned buffers at the same element offset) become line-aligned, byte codes included;
+// any other stream is still accessed correctly, just unaligned.
+constexpr uint32_t kAlignElems = 128;
+__device__ __forceinline__ uint64_t aligned_start(uint64_t pos, uint64_t end, uint32_t phase) {
+    const uint32_t mis = (uint32_t)(pos + phase) & (kAlignElems - 1);
+    const uint64_t a = mis ? pos + (kAlignElems - mis) : pos;
+    return a < end ? a : end;
+}
 
 // Index of the segment that holds element `pos` (pos < seg[T]): the smallest s with seg[s+1] > pos.
 __device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg, uint32_t T,

@@ -166,6 +166,7 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src s
     Src src = src_in;
     src.bind(s_src);
     const int tid = threadIdx.x;
+    const uint32_t phase = work.phase;
     Claimer claimer(work);
     Share sh;
     while (claimer.claim(work, N, sh, &s_claim)) {
@@ -181,7 +182,17 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src s
         src.enter_segment(s);
         const double c64 = (double)pivot[s];
         double s1 = 0.0, s2 = 0.0;
-        uint64_t base = pos;
+        auto single = [&](uint64_t lo, uint64_t hi) {
+            for (uint64_t i = lo + tid; i < hi; i += kThreads) {
+                float v = src.value1(i);
+                if (kWriteAcc) acc_out[i] = v;
+                double d = (double)v - c64;
+                s1 += d;
+                s2 = fma(d, d, s2);
+            }
+        };
+        uint64_t base = aligned_start(pos, sub_end, phase);
+        single(pos, base);
         for (; base + kIter <= sub_end; base += kIter) {
             typename Src::Raw raw[kUnroll];
 #pragma unroll
@@ -199,13 +210,7 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src s
                 }
             }
         }
-        for (uint64_t i = base + tid; i < sub_end; i += kThreads) {
-            float v = src.value1(i);
-            if (kWriteAcc) acc_out[i] = v;
-            double d = (double)v - c64;
-            s1 += d;
-            s2 = fma(d, d, s2);
-        }
+        single(base, sub_end);
         block_sum2(s1, s2, s_red);
         if (tid == 0) {
             atomicAdd(&stats[2 * (size_t)s], s1);
@@ -325,6 +330,7 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src s
     src.bind(s_src);
     const int tid = threadIdx.x;
     unsigned long long* const s_bin = s_bin_all + (tid & (kCopies - 1));   // this lane's copy
+    const uint32_t phase = work.phase;
     Claimer claimer(work);
     Share sh;
     while (claimer.claim(work, N, sh, &s_claim)) {
@@ -358,7 +364,12 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src s
                 bin_c += c;
             }
         };
-        uint64_t base = pos;
+        auto single = [&](uint64_t lo, uint64_t hi) {
+            for (uint64_t i = lo + tid; i < hi; i += kThreads)
+                codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far);
+        };
+        uint64_t base = aligned_start(pos, sub_end, phase);
+        single(pos, base);
         int since_flush = 0;
         for (; base + kIter <= sub_end; base += kIter) {
             typename Src::Raw raw[kUnroll];
@@ -378,8 +389,7 @@ __global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src s
                 __syncthreads();
             }
         }
-        for (uint64_t i = base + tid; i < sub_end; i += kThreads)
-            codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far);
+        single(base, sub_end);
         __syncthreads();
         drain(false);
         if (bin_c) {

@@ -68,7 +68,17 @@ struct Grid {
 #define DILOCO_CHUNK_ITERS 32
 #endif
 constexpr uint64_t kMaxChunkIters = DILOCO_CHUNK_ITERS;
-inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long long* counter) {
+inline uint32_t host_phase(const void* p, int elem_bytes) {
+    return (uint32_t)((uintptr_t)p / (uintptr_t)elem_bytes) & (kAlignElems - 1);
+}
+inline void set_phase(Work& w, uint64_t N, uint32_t phase) {
+    w.phase = phase;
+    w.origin = (kAlignElems - phase) & (kAlignElems - 1);
+    const uint64_t body = N > w.origin ? N - w.origin : 0;
+    w.num_chunks = (body + w.chunk - 1) / w.chunk;
+    if (w.num_chunks < 1) w.num_chunks = 1;
+}
+inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long long* counter, uint32_t phase) {
     Grid g;
     const uint64_t resident = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
     uint64_t iters = (N + kIter - 1) / kIter;
@@ -78,7 +88,7 @@ inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long 
     if (chunk_iters > kMaxChunkIters) chunk_iters = kMaxChunkIters;
     g.work.counter = counter;
     g.work.chunk = chunk_iters * kIter;
-    g.work.num_chunks = (N + g.work.chunk - 1) / g.work.chunk;
+    set_phase(g.work, N, phase);
     g.blocks = (uint32_t)(g.work.num_chunks < resident ? g.work.num_chunks : resident);
     if (g.blocks < 1) g.blocks = 1;
     return g;
@@ -98,7 +108,7 @@ DILOCO_DECLARE_REDUCE_GROUP(3)
 
 // One contiguous share per block, no counter: the in-place outer step runs fastest as long walks
 // (measured: 28 ms with one share per block or 2M-element chunks, 32 ms with 128K-element chunks).
-inline Grid plan_static(uint64_t N, int num_cus, int blocks_per_cu) {
+inline Grid plan_static(uint64_t N, int num_cus, int blocks_per_cu, uint32_t phase) {
     Grid g;
     uint64_t want = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
     uint64_t iters = (N + kIter - 1) / kIter;
@@ -106,7 +116,7 @@ inline Grid plan_static(uint64_t N, int num_cus, int blocks_per_cu) {
     if (want > iters) want = iters;
     g.work.counter = nullptr;
     g.work.chunk = (iters + want - 1) / want * kIter;
-    g.work.num_chunks = (N + g.work.chunk - 1) / g.work.chunk;
+    set_phase(g.work, N, phase);
     g.blocks = (uint32_t)g.work.num_chunks;
     if (g.blocks < 1) g.blocks = 1;
     return g;

@@ -51,8 +51,11 @@ __global__ __launch_bounds__(kThreads) void outer_fp32_kernel(float* theta, floa
     const int tid = threadIdx.x;
     Claimer claimer(work);
     Share sh;
+    const uint32_t phase = work.phase;
     while (claimer.claim(work, N, sh, &s_claim)) {
-    uint64_t base = sh.begin;
+    uint64_t base = aligned_start(sh.begin, sh.end, phase);
+    for (uint64_t i = sh.begin + tid; i < base; i += kThreads)
+        nesterov1<kOut>(theta, mom, local_out, i, delta[i], lr, beta);
     for (; base + kIter <= sh.end; base += kIter) {
         f32x4 g[kUnroll], m[kUnroll], th[kUnroll];
 #pragma unroll
@@ -98,7 +101,9 @@ __global__ __launch_bounds__(kThreads) void outer_coded_kernel(float* theta, flo
         __syncthreads();
         s_lut[tid] = lut[(size_t)s * kBuckets + tid];
         __syncthreads();
-        uint64_t base = pos;
+        uint64_t base = aligned_start(pos, sub_end, work.phase);
+        for (uint64_t i = pos + tid; i < base; i += kThreads)
+            nesterov1<kOut>(theta, mom, local_out, i, s_lut[codes[i]], lr, beta);
         for (; base + kIter <= sub_end; base += kIter) {
             uint32_t c[kUnroll];
             f32x4 m[kUnroll], th[kUnroll];
