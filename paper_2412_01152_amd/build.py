@@ -10,7 +10,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
-OUT = os.path.join(HERE, "libdiloco_mi355.so")
+OUT = os.environ.get("DILOCO_OUT", os.path.join(HERE, "libdiloco_mi355.so"))
+BUILD = os.environ.get("DILOCO_BUILD_DIR", BUILD)
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

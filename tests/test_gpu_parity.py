@@ -336,3 +336,58 @@ def test_chained_config0(B, oracle_mod):
     assert np.all(diff[same] <= 1e-5 * scale[same])
     assert np.all(diff[~same] <= 0.7 * 1.9 * 1.01 * w2 + 1e-5 * scale[~same])   # a flipped code moves by one bucket
     say(f"[chained] config0: stage-2 flips={flips}")
+
+
+# ---------------------------------------------------------------------------------------------
+# data-dependent conditions are reported per segment, never as a fault
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bad", [float("nan"), float("inf"), -float("inf")])
+def test_nonfinite_input_is_flagged_not_fatal(B, oracle_mod, bad):
+    sizes = [20_000, 5_000, 70_000]
+    theta, locals_, off = synth.make_inputs(sizes, 1, device=DEV)
+    local = locals_[0]
+    local[off[1] + 17] = bad                                   # poisons segment 1 only
+    codes, luts, qp = B.pseudograd_quantize(theta, local, off)
+    torch.cuda.synchronize()
+    g_qp = B.qparams_to_numpy(qp)
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(t2n(theta), t2n(local), off)
+    assert list(g_qp["status"]) == list(o_qp["status"])
+    assert g_qp["status"][1] & B.STATUS_NONFINITE and g_qp["status"][0] == 0 and g_qp["status"][2] == 0
+    # the clean segments are unaffected and still match the oracle exactly
+    for s in (0, 2):
+        a, b = off[s], off[s + 1]
+        check_qparams(g_qp[s:s + 1], o_qp[s:s + 1])
+        check_codes(t2n(codes[a:b]), o_codes[a:b], o_d[a:b], [0, b - a], o_qp[s:s + 1])
+        check_luts(t2n(luts[s]), o_luts[s], o_codes[a:b], [0, b - a], o_qp[s:s + 1])
+    # a later call on clean data is unaffected (no state is kept)
+    local[off[1] + 17] = theta[off[1] + 17]
+    _check_stage1(B, oracle_mod, theta, local, off, "after non-finite")
+
+
+def test_large_mean_small_spread(B, oracle_mod):
+    """Statistics about a pivot: a pseudo-gradient whose mean is 10^4 standard deviations."""
+    sizes = [300_000, 4096]
+    theta, locals_, off = synth.make_inputs(sizes, 1, device=DEV)
+    local = locals_[0] - 10.0                                  # d = theta - local has mean ~ +10, std ~ 2e-3
+    _check_stage1(B, oracle_mod, theta, local, off, "large mean")
+
+
+def test_few_distinct_values_reconstruct(B, oracle_mod):
+    """A tensor with 16 well separated levels: every bucket holds one distinct value.  The oracle
+    decodes it bit-exactly; the library's fixed-point bucket sums round each offset to 2^-22 of a
+    bucket width, so it decodes to within that (far inside the 1e-6 codebook tolerance)."""
+    n = 160_000
+    levels = ((torch.arange(16, device=DEV, dtype=torch.float32) - 7.5) * 1.33e-4)
+    d = levels[torch.randint(0, 16, (n,), device=DEV, generator=torch.Generator(device=DEV).manual_seed(5))]
+    theta = torch.zeros(n, dtype=torch.float32, device=DEV)
+    local = -d                                                 # theta - local = d exactly
+    codes, luts, qp = B.pseudograd_quantize(theta, local, [0, n])
+    torch.cuda.synchronize()
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(t2n(theta), t2n(local), [0, n])
+    assert np.array_equal(o_luts[0][o_codes], t2n(d))          # the oracle is exact here
+    assert np.array_equal(t2n(codes), o_codes)
+    w = 12.0 * float(o_qp["std"][0]) / 256.0
+    dec = t2n(luts)[0][t2n(codes)]
+    assert np.abs(dec.astype(np.float64) - t2n(d)).max() <= 2.0 ** -21 * w
+    check_luts(t2n(luts), o_luts, o_codes, [0, n], o_qp)
