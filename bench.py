@@ -61,6 +61,9 @@ def main():
                     help="config 4 only: the 13 coded contributions of each chunk arrive from pinned host memory on "
                          "a copy stream while the previous chunk is reduced; reports the reduce time with and "
                          "without the concurrent transfer")
+    ap.add_argument("--study", choices=["ring"], default=None,
+                    help="ring: error and time of the per-hop ring reduce (requantised at every hop) against the "
+                         "one-shot W-way reduce, on one decoder layer (config 1's shape)")
     ap.add_argument("--cpu-layers", type=int, default=4,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
@@ -80,6 +83,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.study == "ring":
+        return study_ring(args, np, torch, B, synth, dev)
     cfg = args.config
     if cfg == 3:
         return bench_config3(args, np, torch, B, synth, dev)
@@ -233,6 +238,57 @@ def main():
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(result), flush=True)
+
+
+def study_ring(args, np, torch, B, synth, dev):
+    """Section 2.2's ring, hop by hop (dequantise the incoming chunk, add the local fp32 data,
+    requantise, forward; W quantisations on the way) against the one-shot reduce (every contribution
+    quantised once, one requantisation).  Data: one decoder layer (9 tensors, 218,112,000 elements),
+    Gaussian, mixture and Student-t pseudo-gradients, W workers.  Error = rms(dequantised result - exact average) / std of the
+    exact average, exact = fp64 mean of the W fp32 pseudo-gradients (evaluation only, with torch)."""
+    from paper_2412_01152_amd import ring
+    sizes = synth.config_segment_sizes(1)
+    off = synth.offsets_from_sizes(sizes)
+    N, T = off[-1], len(sizes)
+    theta = torch.empty(N, dtype=torch.float32, device=dev)
+    synth.fill_theta_outer(theta)
+    ws = B.new_workspace(T, dev)
+    rows = []
+    for kind, W in [(k, w) for k in ("normal", "mixture", "student_t3") for w in (2, 4, 8, 14)]:
+        d = []
+        for p in range(W):
+            x = torch.empty(N, dtype=torch.float32, device=dev)
+            synth.fill_theta_local(x, theta, p, kind)
+            x.sub_(theta).neg_()                              # theta_outer - theta_local
+            d.append(x)
+        exact = torch.zeros(N, dtype=torch.float64, device=dev)
+        for x in d:
+            exact += x
+        exact /= W
+        sd = float(exact.std())
+
+        def run(fn):
+            fn(d, off, ws)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            out = fn(d, off, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            val = ring.dequantise(out[0], out[1], off, workspace=ws)
+            err = float(torch.sqrt(torch.mean((val.double() - exact) ** 2))) / sd
+            return err, e0.elapsed_time(e1)
+
+        err_ring, ms_ring = run(ring.ring_reduce)
+        err_one, ms_one = run(ring.one_shot_reduce)
+        rows.append({"delta": kind, "W": W, "rms_error_over_std": {"ring": round(err_ring, 5), "one_shot": round(err_one, 5)},
+                     "ms": {"ring": round(ms_ring, 3), "one_shot": round(ms_one, 3)}})
+        log(f"[study] {kind:10s} W={W:2d}: rms error / std  ring {err_ring:.5f}  one-shot {err_one:.5f}  "
+            f"({err_ring / err_one:.2f}x);  time ring {ms_ring:.2f} ms  one-shot {ms_one:.2f} ms (both include quantising "
+            f"the W fp32 inputs)")
+        del d, exact
+    print(json.dumps({"study": "ring hop-by-hop vs one-shot reduce", "elements": N, "segments": T, "rows": rows}),
+          flush=True)
 
 
 def measure_copy_kernel(torch, src_buf, dev):
