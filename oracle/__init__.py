@@ -50,6 +50,16 @@ def set_num_threads(t: int) -> None:
     lib().oracle_set_num_threads(int(t))
 
 
+PAPER_RANGE_SIGMAS = 6.0          # Section 2.2: the range is mean +- 6 standard deviations
+
+
+def _variant(range_sigmas, codebook):
+    """The quantiser's two knobs as C arguments; the defaults are the paper's."""
+    if codebook not in ("mean", "midpoint"):
+        raise ValueError(codebook)
+    return ctypes.c_double(float(range_sigmas)), ctypes.c_int(int(codebook == "midpoint"))
+
+
 def _p(a):
     return ctypes.c_void_p(a.ctypes.data) if a is not None else ctypes.c_void_p(0)
 
@@ -78,13 +88,14 @@ def pseudograd(theta_outer, theta_local, local_is_bf16=False):
     return d
 
 
-def quantize(x):
+def quantize(x, range_sigmas=PAPER_RANGE_SIGMAS, codebook="mean"):
     """Q on one tensor -> (codes u8[n], lut f32[256], qparams record)."""
     x = _chk(x, np.float32, "x")
     codes = np.empty(x.size, dtype=np.uint8)
     lut = np.empty(256, dtype=np.float32)
     qp = np.zeros(1, dtype=QPARAMS_DTYPE)
-    lib().oracle_quantize(_p(x), ctypes.c_uint64(x.size), _p(codes), _p(lut), _p(qp))
+    lib().oracle_quantize(_p(x), ctypes.c_uint64(x.size), *_variant(range_sigmas, codebook), _p(codes), _p(lut),
+                          _p(qp))
     return codes, lut, qp[0]
 
 
@@ -96,18 +107,20 @@ def dequantize(codes, lut):
     return out
 
 
-def quantize_segments(x, seg_offsets):
+def quantize_segments(x, seg_offsets, range_sigmas=PAPER_RANGE_SIGMAS, codebook="mean"):
     x = _chk(x, np.float32, "x")
     so = _segs(seg_offsets, x.size)
     T = so.size - 1
     codes = np.empty(x.size, dtype=np.uint8)
     luts = np.empty((T, 256), dtype=np.float32)
     qps = np.zeros(T, dtype=QPARAMS_DTYPE)
-    lib().oracle_quantize_segments(_p(x), _p(so), ctypes.c_uint32(T), _p(codes), _p(luts), _p(qps))
+    lib().oracle_quantize_segments(_p(x), _p(so), ctypes.c_uint32(T), *_variant(range_sigmas, codebook),
+                                   _p(codes), _p(luts), _p(qps))
     return codes, luts, qps
 
 
-def pseudograd_quantize(theta_outer, theta_local, seg_offsets, local_is_bf16=False):
+def pseudograd_quantize(theta_outer, theta_local, seg_offsets, local_is_bf16=False,
+                        range_sigmas=PAPER_RANGE_SIGMAS, codebook="mean"):
     """Stage 1 -> (codes, luts[T][256], qparams[T], d) where d is the fp32 pseudo-gradient."""
     to = _chk(theta_outer, np.float32, "theta_outer")
     tl = _chk(theta_local, np.uint16 if local_is_bf16 else np.float32, "theta_local")
@@ -119,12 +132,13 @@ def pseudograd_quantize(theta_outer, theta_local, seg_offsets, local_is_bf16=Fal
     luts = np.empty((T, 256), dtype=np.float32)
     qps = np.zeros(T, dtype=QPARAMS_DTYPE)
     lib().oracle_pseudograd_quantize(_p(to), _p(tl), ctypes.c_int(int(local_is_bf16)),
-                                     ctypes.c_uint64(to.size), _p(so), ctypes.c_uint32(T), _p(d),
-                                     _p(codes), _p(luts), _p(qps))
+                                     ctypes.c_uint64(to.size), _p(so), ctypes.c_uint32(T),
+                                     *_variant(range_sigmas, codebook), _p(d), _p(codes), _p(luts), _p(qps))
     return codes, luts, qps, d
 
 
-def reduce(peer_codes, peer_luts, seg_offsets, divisor, local_fp32=None):
+def reduce(peer_codes, peer_luts, seg_offsets, divisor, local_fp32=None,
+           range_sigmas=PAPER_RANGE_SIGMAS, codebook="mean"):
     """Stage 2 -> (acc f32[n], codes_out, luts_out, qparams_out).
 
     peer_codes: list of W uint8[n]; peer_luts: list of W float32[T][256]."""
@@ -150,8 +164,8 @@ def reduce(peer_codes, peer_luts, seg_offsets, divisor, local_fp32=None):
     luts = np.empty((T, 256), dtype=np.float32)
     qps = np.zeros(T, dtype=QPARAMS_DTYPE)
     lib().oracle_reduce(code_ptrs, lut_ptrs, ctypes.c_uint32(W), _p(loc), ctypes.c_uint32(divisor),
-                        ctypes.c_uint64(n), _p(so), ctypes.c_uint32(T), _p(acc), _p(codes),
-                        _p(luts), _p(qps))
+                        ctypes.c_uint64(n), _p(so), ctypes.c_uint32(T), *_variant(range_sigmas, codebook),
+                        _p(acc), _p(codes), _p(luts), _p(qps))
     return acc, codes, luts, qps
 
 

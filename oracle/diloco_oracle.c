@@ -46,7 +46,10 @@
 #define ORACLE_STATUS_EMPTY 4u
 
 #define ORACLE_NUM_BUCKETS 256
-#define ORACLE_RANGE_SIGMAS 6.0
+/* The paper's quantiser has range_sigmas = 6 and the bucket-mean codebook (midpoint_codebook = 0).
+ * Both are arguments so that the variants the paper only argues about qualitatively (Section 2.2:
+ * why clip, why a codebook of bucket means) can be measured: another clipping width, and a codebook
+ * of bucket midpoints.  Every caller that reproduces the paper passes 6.0 and 0. */
 
 typedef struct {
     double mean;     /* mu of the segment (fp64) */
@@ -107,7 +110,8 @@ void oracle_pseudograd(const float* theta_outer, const void* theta_local, int lo
 
 /* Section 2.2, quantisation list, on one tensor x[0..n).
  * Writes codes[n], lut[256] and the statistics record. */
-void oracle_quantize(const float* x, uint64_t n, uint8_t* codes, float* lut, oracle_qparams* qp) {
+void oracle_quantize(const float* x, uint64_t n, double range_sigmas, int midpoint_codebook,
+                     uint8_t* codes, float* lut, oracle_qparams* qp) {
     oracle_qparams r;
     memset(&r, 0, sizeof r);
     r.n = n;
@@ -133,8 +137,8 @@ void oracle_quantize(const float* x, uint64_t n, uint8_t* codes, float* lut, ora
     if (!isfinite(mu) || !isfinite(sigma)) r.status |= ORACLE_STATUS_NONFINITE;
 
     /* items 2 and 3: range [mu - 6 sigma, mu + 6 sigma] cut into 256 equal buckets */
-    double lo64 = mu - ORACLE_RANGE_SIGMAS * sigma;
-    double w64 = (2.0 * ORACLE_RANGE_SIGMAS * sigma) / (double)ORACLE_NUM_BUCKETS;
+    double lo64 = mu - range_sigmas * sigma;
+    double w64 = (2.0 * range_sigmas * sigma) / (double)ORACLE_NUM_BUCKETS;
     float lo = (float)lo64;
     float inv_w = 0.0f;
     if (sigma > 0.0) {
@@ -167,7 +171,7 @@ void oracle_quantize(const float* x, uint64_t n, uint8_t* codes, float* lut, ora
         bcnt[k] += 1;
     }
     for (int k = 0; k < ORACLE_NUM_BUCKETS; ++k) {
-        if (bcnt[k] > 0)
+        if (bcnt[k] > 0 && !midpoint_codebook)
             lut[k] = (float)(bsum[k] / (double)bcnt[k]);
         else
             lut[k] = (float)(lo64 + ((double)k + 0.5) * w64);
@@ -183,11 +187,13 @@ void oracle_dequantize(const uint8_t* codes, const float* lut, uint64_t n, float
 /* Q applied segment by segment: segment s covers [seg_offsets[s], seg_offsets[s+1]).
  * luts is [T][256], qps is [T]. */
 void oracle_quantize_segments(const float* x, const uint64_t* seg_offsets, uint32_t T,
-                              uint8_t* codes, float* luts, oracle_qparams* qps) {
+                              double range_sigmas, int midpoint_codebook, uint8_t* codes,
+                              float* luts, oracle_qparams* qps) {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t s = 0; s < (int32_t)T; ++s) {
         uint64_t a = seg_offsets[s], b = seg_offsets[s + 1];
-        oracle_quantize(x + a, b - a, codes + a, luts + (size_t)s * ORACLE_NUM_BUCKETS, &qps[s]);
+        oracle_quantize(x + a, b - a, range_sigmas, midpoint_codebook, codes + a,
+                        luts + (size_t)s * ORACLE_NUM_BUCKETS, &qps[s]);
     }
 }
 
@@ -195,10 +201,12 @@ void oracle_quantize_segments(const float* x, const uint64_t* seg_offsets, uint3
  * (it holds the pseudo-gradient on return). */
 void oracle_pseudograd_quantize(const float* theta_outer, const void* theta_local,
                                 int local_is_bf16, uint64_t N, const uint64_t* seg_offsets,
-                                uint32_t T, float* d_scratch, uint8_t* codes, float* luts,
+                                uint32_t T, double range_sigmas, int midpoint_codebook,
+                                float* d_scratch, uint8_t* codes, float* luts,
                                 oracle_qparams* qps) {
     oracle_pseudograd(theta_outer, theta_local, local_is_bf16, N, d_scratch);
-    oracle_quantize_segments(d_scratch, seg_offsets, T, codes, luts, qps);
+    oracle_quantize_segments(d_scratch, seg_offsets, T, range_sigmas, midpoint_codebook, codes, luts,
+                             qps);
 }
 
 /* Stage 2: the local reduction step of the quantised all-reduce.
@@ -208,8 +216,9 @@ void oracle_pseudograd_quantize(const float* theta_outer, const void* theta_loca
  * peer_luts[p] is [T][256].  acc is [n] (required; receives the averaged fp32 values). */
 void oracle_reduce(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,
                    const float* local_fp32, uint32_t divisor, uint64_t n,
-                   const uint64_t* seg_offsets, uint32_t T, float* acc, uint8_t* codes_out,
-                   float* luts_out, oracle_qparams* qps_out) {
+                   const uint64_t* seg_offsets, uint32_t T, double range_sigmas,
+                   int midpoint_codebook, float* acc, uint8_t* codes_out, float* luts_out,
+                   oracle_qparams* qps_out) {
     float fdiv = (float)divisor;
     (void)n; /* seg_offsets[T] == n */
     for (uint32_t s = 0; s < T; ++s) {
@@ -224,7 +233,8 @@ void oracle_reduce(const uint8_t* const* peer_codes, const float* const* peer_lu
             acc[i] = v / fdiv;
         }
     }
-    oracle_quantize_segments(acc, seg_offsets, T, codes_out, luts_out, qps_out);
+    oracle_quantize_segments(acc, seg_offsets, T, range_sigmas, midpoint_codebook, codes_out,
+                             luts_out, qps_out);
 }
 
 /* Stage 3: outer optimiser, SGD with Nesterov momentum.

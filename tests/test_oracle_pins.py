@@ -190,8 +190,9 @@ def test_outlier_clips_into_end_bucket(oracle_mod):
 # P7: brute force in exact rational arithmetic on tiny tensors
 # ---------------------------------------------------------------------------------------------
 
-def _exact_quantize(x):
-    """Section 2.2 in exact arithmetic: returns codes, exact bucket means, distance to nearest edge."""
+def _exact_quantize(x, range_sigmas=6, midpoint=False):
+    """Section 2.2 in exact arithmetic: returns codes, exact codebook entries of the populated buckets
+    (bucket means, or bucket midpoints for the midpoint variant), distance to the nearest edge."""
     getcontext().prec = 60
     xs = [Fraction(float(v)) for v in x]
     n = len(xs)
@@ -200,8 +201,8 @@ def _exact_quantize(x):
     sigma = Decimal(var.numerator) / Decimal(var.denominator)
     sigma = sigma.sqrt()
     sigma = Fraction(sigma)
-    lo = mu - 6 * sigma
-    w = 12 * sigma / 256
+    lo = mu - range_sigmas * sigma
+    w = 2 * range_sigmas * sigma / 256
     codes, dist = [], []
     for v in xs:
         t = (v - lo) / w
@@ -211,7 +212,7 @@ def _exact_quantize(x):
     means = {}
     for k in set(codes):
         vals = [v for v, c in zip(xs, codes) if c == k]
-        means[k] = sum(vals) / len(vals)
+        means[k] = lo + (k + Fraction(1, 2)) * w if midpoint else sum(vals) / len(vals)
     return codes, means, dist, mu, sigma
 
 
@@ -235,9 +236,76 @@ def test_brute_force_exact_rational(oracle_mod, seed):
         assert abs(float(lut[k]) - float(ref)) <= np.spacing(np.abs(ref))
 
 
+@pytest.mark.parametrize("range_sigmas,codebook", [(4, "mean"), (8, "mean"), (3, "mean"), (6, "midpoint"),
+                                                   (4, "midpoint")])
+@pytest.mark.parametrize("seed", range(3))
+def test_brute_force_variants(oracle_mod, seed, range_sigmas, codebook):
+    """The quantiser's two knobs (clipping width, codebook of bucket midpoints) against exact arithmetic."""
+    rng = np.random.default_rng(300 + seed)
+    n = int(rng.integers(8, 64))
+    while True:
+        x = (rng.normal(0, 1e-3, n) + rng.normal(0, 2e-3)).astype(np.float32)
+        codes_e, lut_e, dist, mu, sigma = _exact_quantize(x, range_sigmas, codebook == "midpoint")
+        if min(dist) > Fraction(1, 1000):
+            break
+    codes, lut, qp = oracle_mod.quantize(x, range_sigmas=range_sigmas, codebook=codebook)
+    assert list(codes) == codes_e
+    for k, m in lut_e.items():
+        ref = np.float32(float(m))
+        assert abs(float(lut[k]) - float(ref)) <= np.spacing(np.abs(ref))
+
+
+def test_variant_defaults_are_the_papers(oracle_mod):
+    x = _mixture(50_000, seed=21)
+    a = oracle_mod.quantize(x)
+    b = oracle_mod.quantize(x, range_sigmas=6.0, codebook="mean")
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and a[2] == b[2]
+
+
+def test_midpoint_codebook_keeps_codes_but_not_the_sum(oracle_mod):
+    """The codebook does not influence the codes; bucket means preserve the tensor's sum, midpoints of
+    a skewed tensor do not (the reason Section 2.2 gives for the codebook of averages)."""
+    rng = np.random.default_rng(22)
+    x = rng.exponential(1e-3, 200_000).astype(np.float32)
+    c_mean, l_mean, qp = oracle_mod.quantize(x)
+    c_mid, l_mid, _ = oracle_mod.quantize(x, codebook="midpoint")
+    assert np.array_equal(c_mean, c_mid)
+    w = 12 * qp["std"] / 256
+    lo = qp["mean"] - 6 * qp["std"]
+    assert np.allclose(l_mid, lo + (np.arange(256) + 0.5) * w, rtol=1e-6, atol=0)
+    total = x.astype(np.float64).sum()
+    assert abs(l_mean[c_mean].astype(np.float64).sum() - total) <= 1e-6 * abs(total)
+    assert abs(l_mid[c_mid].astype(np.float64).sum() - total) > 1e-4 * abs(total)
+    inside = (c_mid > 0) & (c_mid < 255)
+    assert np.all(np.abs(x[inside] - l_mid[c_mid[inside]]) <= 0.5 * w * (1 + 1e-4))
+
+
 # ---------------------------------------------------------------------------------------------
 # P8: Gaussian closed form
 # ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("c", [4.0, 8.0])
+def test_gaussian_closed_form_other_clip_widths(oracle_mod, c):
+    """Occupancy and error for a range of +-c sigma: inner buckets follow the normal CDF with step
+    2c/256, the end buckets also hold the clipped tails (2 Phi(-c) of the values in total)."""
+    n = 1 << 22
+    s = 1e-3
+    x = _gauss(n, std=s, seed=11)
+    codes, lut, qp = oracle_mod.quantize(x, range_sigmas=c)
+    phi = lambda z: 0.5 * (1 + math.erf(z / math.sqrt(2)))
+    counts = np.bincount(codes, minlength=256)
+    step = 2 * c / 256.0
+    for k in range(256):
+        a = -math.inf if k == 0 else (k - 128) * step
+        b = math.inf if k == 255 else (k - 127) * step
+        p = phi(b) - phi(a) if k not in (0, 255) else (phi(b) if k == 0 else 1 - phi(a))
+        se = math.sqrt(n * p * (1 - p))
+        assert abs(counts[k] - n * p) <= 5 * se + 2, k
+    xh = oracle_mod.dequantize(codes, lut)
+    inside = np.abs(x) < (c - step) * s
+    rms = math.sqrt(np.mean((x[inside].astype(np.float64) - xh[inside]) ** 2))
+    assert rms / s == pytest.approx(step / math.sqrt(12), rel=0.03)
+
 
 def test_gaussian_bucket_occupancy_and_rms(oracle_mod):
     n = 1 << 22
