@@ -56,6 +56,11 @@ extern "C" {
 #define DILOCO_ERR_WORKSPACE (-4)   /* workspace smaller than diloco_workspace_bytes(T)    */
 #define DILOCO_ERR_DTYPE (-5)       /* unknown dtype flag                                  */
 
+#define DILOCO_CODEBOOK_MEAN 0u      /* codebook entry = average of the bucket's values (the paper's) */
+#define DILOCO_CODEBOOK_MIDPOINT 1u  /* codebook entry = centre of the bucket                         */
+#define DILOCO_MIN_RANGE_SIGMAS 0.5  /* bounds on range_sigmas of the *_variant calls                 */
+#define DILOCO_MAX_RANGE_SIGMAS 64.0
+
 #define DILOCO_STATUS_DEGENERATE 1u /* sigma == 0 (or 1/width not finite): all codes 0, lut[0] = mean */
 #define DILOCO_STATUS_NONFINITE 2u  /* NaN/Inf reached the statistics; codes unspecified            */
 #define DILOCO_STATUS_EMPTY 4u      /* segment has no elements; lut is all zeros                     */
@@ -135,6 +140,33 @@ int32_t int8_reduce_chunk(const uint8_t* const* peer_codes, const float* const* 
                           const uint64_t* seg_offsets, uint32_t T, float* acc_out,
                           uint8_t* codes_out, float* lut_out, diloco_qparams* qparams_out,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two quantising calls with the quantiser's two constants as arguments.  Section 2.2 fixes a
+ * clipping range of +-6 standard deviations and a codebook of bucket averages, and argues for both
+ * only in words (outliers are clipped to keep the buckets narrow; averages instead of centres lower
+ * the error); these calls let the alternatives be measured on the same kernels.
+ *     range_sigmas   half-width c of the range [mean - c std, mean + c std], in
+ *                    [DILOCO_MIN_RANGE_SIGMAS, DILOCO_MAX_RANGE_SIGMAS] (else DILOCO_ERR_SIZE);
+ *                    lo = fp32(mean - c std), inv_w = fp32(256 / (2 c std))
+ *     codebook       DILOCO_CODEBOOK_MEAN or DILOCO_CODEBOOK_MIDPOINT (else DILOCO_ERR_DTYPE); with
+ *                    MIDPOINT lut[k] = fp32(mean - c std + (k + 1/2) * 2 c std / 256) for every k,
+ *                    clipped values included
+ * With range_sigmas = 6.0 and DILOCO_CODEBOOK_MEAN they are the calls above, bit for bit.  All other
+ * arguments, layouts and error behaviour are those of the calls above.
+ */
+int32_t diloco_pseudograd_quantize_variant(const float* theta_outer, const void* theta_local,
+                                           int32_t local_dtype, uint64_t N,
+                                           const uint64_t* seg_offsets, uint32_t T, uint8_t* codes_out,
+                                           float* lut_out, diloco_qparams* qparams_out,
+                                           void* workspace, size_t workspace_bytes, void* stream,
+                                           double range_sigmas, uint32_t codebook);
+int32_t int8_reduce_chunk_variant(const uint8_t* const* peer_codes, const float* const* peer_luts,
+                                  uint32_t W, const float* local_fp32, uint32_t divisor, uint64_t n,
+                                  const uint64_t* seg_offsets, uint32_t T, float* acc_out,
+                                  uint8_t* codes_out, float* lut_out, diloco_qparams* qparams_out,
+                                  void* workspace, size_t workspace_bytes, void* stream,
+                                  double range_sigmas, uint32_t codebook);
 
 /*
  * Stage 3.  Outer optimiser step, SGD with Nesterov momentum (Algorithm 1, outer-optimisation

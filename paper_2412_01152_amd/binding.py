@@ -29,7 +29,10 @@ QPARAMS_BYTES = 40
 assert QPARAMS_DTYPE.itemsize == QPARAMS_BYTES
 
 EXPORTS = ("diloco_workspace_bytes", "diloco_strerror", "diloco_pseudograd_quantize",
-           "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes")
+           "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes",
+           "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant")
+
+CODEBOOK_MEAN, CODEBOOK_MIDPOINT = 0, 1
 
 _lib = None
 
@@ -59,6 +62,11 @@ def load() -> ctypes.CDLL:
     lib.diloco_pseudograd_quantize.argtypes = [vp, vp, i32, u64, vp, u32, vp, vp, vp, vp, sz, vp]
     lib.int8_reduce_chunk.restype = i32
     lib.int8_reduce_chunk.argtypes = [vp, vp, u32, vp, u32, u64, vp, u32, vp, vp, vp, vp, vp, sz, vp]
+    f64 = ctypes.c_double
+    lib.diloco_pseudograd_quantize_variant.restype = i32
+    lib.diloco_pseudograd_quantize_variant.argtypes = lib.diloco_pseudograd_quantize.argtypes + [f64, u32]
+    lib.int8_reduce_chunk_variant.restype = i32
+    lib.int8_reduce_chunk_variant.argtypes = lib.int8_reduce_chunk.argtypes + [f64, u32]
     lib.outer_nesterov_step.restype = i32
     lib.outer_nesterov_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u64, f32, f32, vp, i32, vp, sz, vp]
     lib.diloco_profile_passes.restype = i32
@@ -113,6 +121,11 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(stream.cuda_stream)
 
 
+def _variant_args(variant):
+    range_sigmas, codebook = variant
+    return ctypes.c_double(float(range_sigmas)), ctypes.c_uint32(int(codebook))
+
+
 def _local_dtype(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return DTYPE_FP32
@@ -124,8 +137,10 @@ def _local_dtype(t: torch.Tensor) -> int:
 def pseudograd_quantize(theta_outer: torch.Tensor, theta_local: torch.Tensor, seg_offsets,
                         codes_out: Optional[torch.Tensor] = None, lut_out: Optional[torch.Tensor] = None,
                         qparams_out: Optional[torch.Tensor] = None,
-                        workspace: Optional[torch.Tensor] = None, stream=None):
-    """diloco_pseudograd_quantize -> (codes u8[N], lut f32[T,256], qparams bytes[T*40])."""
+                        workspace: Optional[torch.Tensor] = None, stream=None, variant=None):
+    """diloco_pseudograd_quantize -> (codes u8[N], lut f32[T,256], qparams bytes[T*40]).
+
+    variant = (range_sigmas, codebook) calls diloco_pseudograd_quantize_variant instead."""
     lib = load()
     assert theta_outer.dtype == torch.float32
     N = theta_outer.numel()
@@ -136,13 +151,14 @@ def pseudograd_quantize(theta_outer: torch.Tensor, theta_local: torch.Tensor, se
     lut_out = torch.empty((max(T, 0), 256), dtype=torch.float32, device=dev) if lut_out is None else lut_out
     qparams_out = new_qparams(max(T, 0), dev) if qparams_out is None else qparams_out
     workspace = new_workspace(T, dev) if workspace is None else workspace
-    rc = lib.diloco_pseudograd_quantize(_ptr(theta_outer), _ptr(theta_local), _local_dtype(theta_local),
-                                        ctypes.c_uint64(N), ctypes.c_void_p(so.ctypes.data),
-                                        ctypes.c_uint32(T), _ptr(codes_out), _ptr(lut_out),
-                                        _ptr(qparams_out), _ptr(workspace),
-                                        ctypes.c_size_t(workspace.numel()), _stream(stream))
+    fn, name, extra = lib.diloco_pseudograd_quantize, "diloco_pseudograd_quantize", ()
+    if variant is not None:
+        fn, name, extra = lib.diloco_pseudograd_quantize_variant, name + "_variant", _variant_args(variant)
+    rc = fn(_ptr(theta_outer), _ptr(theta_local), _local_dtype(theta_local), ctypes.c_uint64(N),
+            ctypes.c_void_p(so.ctypes.data), ctypes.c_uint32(T), _ptr(codes_out), _ptr(lut_out), _ptr(qparams_out),
+            _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(stream), *extra)
     if rc != 0:
-        raise DilocoError(rc, "diloco_pseudograd_quantize")
+        raise DilocoError(rc, name)
     return codes_out, lut_out, qparams_out
 
 
@@ -150,8 +166,10 @@ def reduce_chunk(peer_codes: List[torch.Tensor], peer_luts: List[torch.Tensor], 
                  local_fp32: Optional[torch.Tensor] = None, acc_out: Optional[torch.Tensor] = None,
                  codes_out: Optional[torch.Tensor] = None, lut_out: Optional[torch.Tensor] = None,
                  qparams_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                 stream=None):
-    """int8_reduce_chunk -> (codes u8[n], lut f32[T,256], qparams bytes[T*40]); acc_out filled if given."""
+                 stream=None, variant=None):
+    """int8_reduce_chunk -> (codes u8[n], lut f32[T,256], qparams bytes[T*40]); acc_out filled if given.
+
+    variant = (range_sigmas, codebook) calls int8_reduce_chunk_variant instead."""
     lib = load()
     W = len(peer_codes)
     assert len(peer_luts) == W
@@ -169,13 +187,15 @@ def reduce_chunk(peer_codes: List[torch.Tensor], peer_luts: List[torch.Tensor], 
     lut_out = torch.empty((T, 256), dtype=torch.float32, device=dev) if lut_out is None else lut_out
     qparams_out = new_qparams(T, dev) if qparams_out is None else qparams_out
     workspace = new_workspace(T, dev) if workspace is None else workspace
-    rc = lib.int8_reduce_chunk(ctypes.cast(code_ptrs, ctypes.c_void_p), ctypes.cast(lut_ptrs, ctypes.c_void_p),
-                               ctypes.c_uint32(W), _ptr(local_fp32), ctypes.c_uint32(divisor),
-                               ctypes.c_uint64(n), ctypes.c_void_p(so.ctypes.data), ctypes.c_uint32(T),
-                               _ptr(acc_out), _ptr(codes_out), _ptr(lut_out), _ptr(qparams_out),
-                               _ptr(workspace), ctypes.c_size_t(workspace.numel()), _stream(stream))
+    fn, name, extra = lib.int8_reduce_chunk, "int8_reduce_chunk", ()
+    if variant is not None:
+        fn, name, extra = lib.int8_reduce_chunk_variant, name + "_variant", _variant_args(variant)
+    rc = fn(ctypes.cast(code_ptrs, ctypes.c_void_p), ctypes.cast(lut_ptrs, ctypes.c_void_p), ctypes.c_uint32(W),
+            _ptr(local_fp32), ctypes.c_uint32(divisor), ctypes.c_uint64(n), ctypes.c_void_p(so.ctypes.data),
+            ctypes.c_uint32(T), _ptr(acc_out), _ptr(codes_out), _ptr(lut_out), _ptr(qparams_out), _ptr(workspace),
+            ctypes.c_size_t(workspace.numel()), _stream(stream), *extra)
     if rc != 0:
-        raise DilocoError(rc, "int8_reduce_chunk")
+        raise DilocoError(rc, name)
     return codes_out, lut_out, qparams_out
 
 

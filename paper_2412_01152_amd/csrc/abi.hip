@@ -92,15 +92,28 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     return e == hipSuccess ? 0 : (int32_t)e;
 }
 
-hipError_t finalize_qparams(const Pass& p, diloco_qparams* qp) {
+// The quantiser's two knobs; the paper's are {6, bucket averages}.
+struct QuantVariant {
+    double range_sigmas;
+    uint32_t codebook;
+};
+constexpr QuantVariant kPaperQuantiser = {6.0, DILOCO_CODEBOOK_MEAN};
+
+int32_t check_variant(double range_sigmas, uint32_t codebook) {
+    if (!(range_sigmas >= DILOCO_MIN_RANGE_SIGMAS && range_sigmas <= DILOCO_MAX_RANGE_SIGMAS)) return DILOCO_ERR_SIZE;
+    if (codebook != DILOCO_CODEBOOK_MEAN && codebook != DILOCO_CODEBOOK_MIDPOINT) return DILOCO_ERR_DTYPE;
+    return DILOCO_OK;
+}
+
+hipError_t finalize_qparams(const Pass& p, const QuantVariant& v, diloco_qparams* qp) {
     hipLaunchKernelGGL(finalize_qparams_kernel, dim3((p.T + 255) / 256), dim3(256), 0, p.stream, p.seg, p.T,
-                       p.stats, p.pivot, qp);
+                       p.stats, p.pivot, v.range_sigmas, qp);
     return hipGetLastError();
 }
 
-hipError_t finalize_lut(const Pass& p, const diloco_qparams* qp, float* lut) {
-    hipLaunchKernelGGL(finalize_lut_kernel, dim3(p.T), dim3(kThreads), 0, p.stream, p.T, qp, p.hsumq, p.hcnt,
-                       p.osum, p.ocnt, lut);
+hipError_t finalize_lut(const Pass& p, const QuantVariant& v, const diloco_qparams* qp, float* lut) {
+    hipLaunchKernelGGL(finalize_lut_kernel, dim3(p.T), dim3(kThreads), 0, p.stream, p.T, v.range_sigmas,
+                       v.codebook, qp, p.hsumq, p.hcnt, p.osum, p.ocnt, lut);
     return hipGetLastError();
 }
 
@@ -177,6 +190,84 @@ hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t
     return e;
 }
 
+int32_t pseudograd_quantize_impl(const float* theta_outer, const void* theta_local, int32_t local_dtype,
+                                 uint64_t N, const uint64_t* seg_offsets, uint32_t T, uint8_t* codes_out,
+                                 float* lut_out, diloco_qparams* qparams_out, void* workspace,
+                                 size_t workspace_bytes, hipStream_t stream, const QuantVariant& v) {
+    if (local_dtype != DILOCO_DTYPE_FP32 && local_dtype != DILOCO_DTYPE_BF16) return DILOCO_ERR_DTYPE;
+    if (!lut_out || !qparams_out) return DILOCO_ERR_NULL;
+    if (N > 0 && (!theta_outer || !theta_local || !codes_out)) return DILOCO_ERR_NULL;
+    int32_t rc = check_segments(seg_offsets, T, N);
+    if (rc) return rc;
+    if (misaligned(theta_outer, 4) || misaligned(theta_local, local_dtype == DILOCO_DTYPE_BF16 ? 2 : 4) ||
+        misaligned(lut_out, 4) || misaligned(qparams_out, 8))
+        return DILOCO_ERR_ALIGN;
+    Pass p;
+    rc = begin_pass(p, N, T, seg_offsets, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    if (local_dtype == DILOCO_DTYPE_BF16) {
+        SrcPseudoGrad<true> src{theta_outer, theta_local};
+        if (N) DILOCO_TRY(run_stats(src, p, host_phase(theta_outer, 4)));
+        DILOCO_TRY(finalize_qparams(p, v, qparams_out));
+        if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
+    } else {
+        SrcPseudoGrad<false> src{theta_outer, theta_local};
+        if (N) DILOCO_TRY(run_stats(src, p, host_phase(theta_outer, 4)));
+        DILOCO_TRY(finalize_qparams(p, v, qparams_out));
+        if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
+    }
+    DILOCO_TRY(finalize_lut(p, v, qparams_out, lut_out));
+    return DILOCO_OK;
+}
+
+int32_t reduce_chunk_impl(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,
+                          const float* local_fp32, uint32_t divisor, uint64_t n, const uint64_t* seg_offsets,
+                          uint32_t T, float* acc_out, uint8_t* codes_out, float* lut_out,
+                          diloco_qparams* qparams_out, void* workspace, size_t workspace_bytes,
+                          hipStream_t stream, const QuantVariant& v) {
+    if (W > DILOCO_MAX_PEERS || (W == 0 && !local_fp32) || divisor == 0) return DILOCO_ERR_SIZE;
+    if (W > 0 && (!peer_codes || !peer_luts)) return DILOCO_ERR_NULL;
+    if (!lut_out || !qparams_out) return DILOCO_ERR_NULL;
+    if (n > 0 && !codes_out) return DILOCO_ERR_NULL;
+    int32_t rc = check_segments(seg_offsets, T, n);
+    if (rc) return rc;
+    ReduceArgs a;
+    memset(&a, 0, sizeof a);
+    a.W = W;
+    for (uint32_t p = 0; p < W; ++p) {
+        if (!peer_luts[p] || (n > 0 && !peer_codes[p])) return DILOCO_ERR_NULL;
+        if (misaligned(peer_luts[p], 4)) return DILOCO_ERR_ALIGN;
+        a.codes[p] = peer_codes[p];
+        a.luts[p] = peer_luts[p];
+    }
+    if (misaligned(local_fp32, 4) || misaligned(acc_out, 4) || misaligned(lut_out, 4) ||
+        misaligned(qparams_out, 8))
+        return DILOCO_ERR_ALIGN;
+    a.local = local_fp32;
+    if ((divisor & (divisor - 1)) == 0) {
+        a.true_div = false;          // multiplying by 2^-j rounds exactly like dividing by 2^j
+        a.div = 1.0f / (float)divisor;
+    } else {
+        a.true_div = true;
+        a.div = (float)divisor;
+    }
+    Pass p;
+    rc = begin_pass(p, n, T, seg_offsets, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    if (n) DILOCO_TRY(reduce_stats(a, p, acc_out));
+    DILOCO_TRY(finalize_qparams(p, v, qparams_out));
+    if (n) {
+        if (acc_out) {
+            SrcF32 src{acc_out};
+            DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
+        } else {
+            DILOCO_TRY(reduce_quant(a, p, qparams_out, codes_out));
+        }
+    }
+    DILOCO_TRY(finalize_lut(p, v, qparams_out, lut_out));
+    return DILOCO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -209,81 +300,43 @@ const char* diloco_strerror(int32_t code) {
 int32_t diloco_pseudograd_quantize(const float* theta_outer, const void* theta_local, int32_t local_dtype,
                                    uint64_t N, const uint64_t* seg_offsets, uint32_t T, uint8_t* codes_out,
                                    float* lut_out, diloco_qparams* qparams_out, void* workspace,
-                                   size_t workspace_bytes, void* stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
-    if (local_dtype != DILOCO_DTYPE_FP32 && local_dtype != DILOCO_DTYPE_BF16) return DILOCO_ERR_DTYPE;
-    if (!lut_out || !qparams_out) return DILOCO_ERR_NULL;
-    if (N > 0 && (!theta_outer || !theta_local || !codes_out)) return DILOCO_ERR_NULL;
-    int32_t rc = check_segments(seg_offsets, T, N);
+                                   size_t workspace_bytes, void* stream) {
+    return pseudograd_quantize_impl(theta_outer, theta_local, local_dtype, N, seg_offsets, T, codes_out, lut_out,
+                                    qparams_out, workspace, workspace_bytes, (hipStream_t)stream,
+                                    kPaperQuantiser);
+}
+
+int32_t diloco_pseudograd_quantize_variant(const float* theta_outer, const void* theta_local,
+                                           int32_t local_dtype, uint64_t N, const uint64_t* seg_offsets,
+                                           uint32_t T, uint8_t* codes_out, float* lut_out,
+                                           diloco_qparams* qparams_out, void* workspace, size_t workspace_bytes,
+                                           void* stream, double range_sigmas, uint32_t codebook) {
+    int32_t rc = check_variant(range_sigmas, codebook);
     if (rc) return rc;
-    if (misaligned(theta_outer, 4) || misaligned(theta_local, local_dtype == DILOCO_DTYPE_BF16 ? 2 : 4) ||
-        misaligned(lut_out, 4) || misaligned(qparams_out, 8))
-        return DILOCO_ERR_ALIGN;
-    Pass p;
-    rc = begin_pass(p, N, T, seg_offsets, workspace, workspace_bytes, stream);
-    if (rc) return rc;
-    if (local_dtype == DILOCO_DTYPE_BF16) {
-        SrcPseudoGrad<true> src{theta_outer, theta_local};
-        if (N) DILOCO_TRY(run_stats(src, p, host_phase(theta_outer, 4)));
-        DILOCO_TRY(finalize_qparams(p, qparams_out));
-        if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
-    } else {
-        SrcPseudoGrad<false> src{theta_outer, theta_local};
-        if (N) DILOCO_TRY(run_stats(src, p, host_phase(theta_outer, 4)));
-        DILOCO_TRY(finalize_qparams(p, qparams_out));
-        if (N) DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
-    }
-    DILOCO_TRY(finalize_lut(p, qparams_out, lut_out));
-    return DILOCO_OK;
+    return pseudograd_quantize_impl(theta_outer, theta_local, local_dtype, N, seg_offsets, T, codes_out, lut_out,
+                                    qparams_out, workspace, workspace_bytes, (hipStream_t)stream,
+                                    QuantVariant{range_sigmas, codebook});
 }
 
 int32_t int8_reduce_chunk(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,
                           const float* local_fp32, uint32_t divisor, uint64_t n, const uint64_t* seg_offsets,
                           uint32_t T, float* acc_out, uint8_t* codes_out, float* lut_out,
-                          diloco_qparams* qparams_out, void* workspace, size_t workspace_bytes,
-                          void* stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
-    if (W > DILOCO_MAX_PEERS || (W == 0 && !local_fp32) || divisor == 0) return DILOCO_ERR_SIZE;
-    if (W > 0 && (!peer_codes || !peer_luts)) return DILOCO_ERR_NULL;
-    if (!lut_out || !qparams_out) return DILOCO_ERR_NULL;
-    if (n > 0 && !codes_out) return DILOCO_ERR_NULL;
-    int32_t rc = check_segments(seg_offsets, T, n);
+                          diloco_qparams* qparams_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return reduce_chunk_impl(peer_codes, peer_luts, W, local_fp32, divisor, n, seg_offsets, T, acc_out, codes_out,
+                             lut_out, qparams_out, workspace, workspace_bytes, (hipStream_t)stream,
+                             kPaperQuantiser);
+}
+
+int32_t int8_reduce_chunk_variant(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,
+                                  const float* local_fp32, uint32_t divisor, uint64_t n,
+                                  const uint64_t* seg_offsets, uint32_t T, float* acc_out, uint8_t* codes_out,
+                                  float* lut_out, diloco_qparams* qparams_out, void* workspace,
+                                  size_t workspace_bytes, void* stream, double range_sigmas, uint32_t codebook) {
+    int32_t rc = check_variant(range_sigmas, codebook);
     if (rc) return rc;
-    ReduceArgs a;
-    memset(&a, 0, sizeof a);
-    a.W = W;
-    for (uint32_t p = 0; p < W; ++p) {
-        if (!peer_luts[p] || (n > 0 && !peer_codes[p])) return DILOCO_ERR_NULL;
-        if (misaligned(peer_luts[p], 4)) return DILOCO_ERR_ALIGN;
-        a.codes[p] = peer_codes[p];
-        a.luts[p] = peer_luts[p];
-    }
-    if (misaligned(local_fp32, 4) || misaligned(acc_out, 4) || misaligned(lut_out, 4) ||
-        misaligned(qparams_out, 8))
-        return DILOCO_ERR_ALIGN;
-    a.local = local_fp32;
-    if ((divisor & (divisor - 1)) == 0) {
-        a.true_div = false;          // multiplying by 2^-j rounds exactly like dividing by 2^j
-        a.div = 1.0f / (float)divisor;
-    } else {
-        a.true_div = true;
-        a.div = (float)divisor;
-    }
-    Pass p;
-    rc = begin_pass(p, n, T, seg_offsets, workspace, workspace_bytes, stream);
-    if (rc) return rc;
-    if (n) DILOCO_TRY(reduce_stats(a, p, acc_out));
-    DILOCO_TRY(finalize_qparams(p, qparams_out));
-    if (n) {
-        if (acc_out) {
-            SrcF32 src{acc_out};
-            DILOCO_TRY(run_quant(src, p, qparams_out, codes_out));
-        } else {
-            DILOCO_TRY(reduce_quant(a, p, qparams_out, codes_out));
-        }
-    }
-    DILOCO_TRY(finalize_lut(p, qparams_out, lut_out));
-    return DILOCO_OK;
+    return reduce_chunk_impl(peer_codes, peer_luts, W, local_fp32, divisor, n, seg_offsets, T, acc_out, codes_out,
+                             lut_out, qparams_out, workspace, workspace_bytes, (hipStream_t)stream,
+                             QuantVariant{range_sigmas, codebook});
 }
 
 int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* delta_fp32,

@@ -7,11 +7,12 @@
 
 namespace diloco {
 
-// Items 1-3 of Section 2.2: mean, sample standard deviation, range [mean - 6 std, mean + 6 std],
-// 256 equal buckets; fp64 throughout, rounded once to the fp32 pair the bucket index uses.
+// Items 1-3 of Section 2.2: mean, sample standard deviation, range [mean - c std, mean + c std]
+// (c = range_sigmas, 6 in the paper), 256 equal buckets; fp64 throughout, rounded once to the fp32
+// pair the bucket index uses.
 __global__ void finalize_qparams_kernel(const uint64_t* __restrict__ seg, uint32_t T,
                                         const double* __restrict__ stats,
-                                        const float* __restrict__ pivot,
+                                        const float* __restrict__ pivot, double range_sigmas,
                                         diloco_qparams* __restrict__ qp) {
     uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= T) return;
@@ -40,8 +41,8 @@ __global__ void finalize_qparams_kernel(const uint64_t* __restrict__ seg, uint32
     r.mean = mean;
     r.std = sd;
     if (!isfinite(mean) || !isfinite(sd)) r.status |= DILOCO_STATUS_NONFINITE;
-    const double lo64 = mean - 6.0 * sd;
-    const double w64 = 12.0 * sd / 256.0;
+    const double lo64 = mean - range_sigmas * sd;
+    const double w64 = (2.0 * range_sigmas * sd) / 256.0;
     r.lo = (float)lo64;
     if (sd > 0.0) {
         float cand = (float)(1.0 / w64);
@@ -54,8 +55,9 @@ __global__ void finalize_qparams_kernel(const uint64_t* __restrict__ seg, uint32
 // Item 4 of Section 2.2: codebook entry = average of the values in the bucket.  The bins hold
 // integer sums of scaled offsets from the bucket centre (plus, for buckets 0 and 255, fp64 sums of
 // the far clipped values), so the average offset is rebuilt in fp64 and the centre added back.
-// An empty bucket gets its midpoint.
-__global__ __launch_bounds__(kThreads) void finalize_lut_kernel(uint32_t T,
+// An empty bucket gets its midpoint; with the midpoint codebook every bucket does.
+__global__ __launch_bounds__(kThreads) void finalize_lut_kernel(uint32_t T, double range_sigmas,
+                                                               uint32_t codebook,
                                                                const diloco_qparams* __restrict__ qp,
                                                                const unsigned long long* __restrict__ hsumq,
                                                                const unsigned long long* __restrict__ hcnt,
@@ -76,11 +78,11 @@ __global__ __launch_bounds__(kThreads) void finalize_lut_kernel(uint32_t T,
         off_sum += osum[2 * (size_t)s + e];
     }
     float out;
-    if (c > 0) {
+    if (c > 0 && codebook == DILOCO_CODEBOOK_MEAN) {
         out = (float)((double)bucket_centre((float)k, q.lo, w) + off_sum / (double)c);
     } else {
-        const double lo64 = q.mean - 6.0 * q.std;
-        const double w64 = 12.0 * q.std / 256.0;
+        const double lo64 = q.mean - range_sigmas * q.std;
+        const double w64 = (2.0 * range_sigmas * q.std) / 256.0;
         out = (float)(lo64 + ((double)k + 0.5) * w64);
     }
     lut[(size_t)s * kBuckets + k] = out;

@@ -86,6 +86,15 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert r(vp(0), pp, 2, vp(0), 2, 16, sp, 1, vp(0), fake, fake, fake, fake, 1 << 20, vp(0)) == -1
     assert r(pp, pp, 2, vp(0), 2, 16, sp, 1, vp(0), fake, fake, fake, fake, 16, vp(0)) == -4
 
+    qv, rv = lib.diloco_pseudograd_quantize_variant, lib.int8_reduce_chunk_variant
+    args_q = (fake, fake, 0, 16, sp, 1, fake, fake, fake, fake, 1 << 20, vp(0))
+    args_r = (pp, pp, 2, vp(0), 2, 16, sp, 1, vp(0), fake, fake, fake, fake, 1 << 20, vp(0))
+    for bad_range in (0.0, 0.25, 65.0, float("nan"), float("inf"), -6.0):
+        assert qv(*args_q, bad_range, 0) == -2
+        assert rv(*args_r, bad_range, 0) == -2
+    assert qv(*args_q, 6.0, 2) == -5 and rv(*args_r, 6.0, 2) == -5
+    assert qv(vp(0), *args_q[1:], 4.0, 1) == -1                 # the ordinary checks still run
+
     o = lib.outer_nesterov_step
     f = ctypes.c_float
     assert o(fake, fake, vp(0), vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -1
