@@ -61,8 +61,9 @@ def main():
                     help="config 4 only: the 13 coded contributions of each chunk arrive from pinned host memory on "
                          "a copy stream while the previous chunk is reduced; reports the reduce time with and "
                          "without the concurrent transfer")
-    ap.add_argument("--study", choices=["ring"], default=None,
-                    help="ring: error and time of the per-hop ring reduce (requantised at every hop) against the "
+    ap.add_argument("--study", choices=["ring", "quantiser"], default=None,
+                    help="quantiser: error of the 8-bit code for other clipping widths, the midpoint codebook and "
+                         "per-row groups, on one decoder layer; ring: error and time of the per-hop ring reduce (requantised at every hop) against the "
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
     ap.add_argument("--cpu-layers", type=int, default=4,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
@@ -85,6 +86,8 @@ def main():
 
     if args.study == "ring":
         return study_ring(args, np, torch, B, synth, dev)
+    if args.study == "quantiser":
+        return study_quantiser(args, np, torch, B, synth, dev)
     cfg = args.config
     if cfg == 3:
         return bench_config3(args, np, torch, B, synth, dev)
@@ -289,6 +292,67 @@ def study_ring(args, np, torch, B, synth, dev):
         del d, exact
     print(json.dumps({"study": "ring hop-by-hop vs one-shot reduce", "elements": N, "segments": T, "rows": rows}),
           flush=True)
+
+
+def study_quantiser(args, np, torch, B, synth, dev):
+    """Section 2.2 argues for its two constants in words only: clipping at 6 sigma keeps the buckets
+    narrow, and a codebook of bucket averages lowers the error.  This measures both on one decoder
+    layer (9 tensors, 218,112,000 elements): rms(decoded - d) / std(d) of a single quantisation, for
+    clipping widths 3..10 sigma, both codebooks, three pseudo-gradient distributions, and with one
+    quantisation group per matrix row instead of per tensor (plain rows, and rows whose scales are
+    spread log-normally, sigma_ln = 1).  All quantisation runs in the library; the error is evaluated
+    with torch."""
+    from paper_2412_01152_amd import ring
+    sizes = synth.config_segment_sizes(1)
+    off = synth.offsets_from_sizes(sizes)
+    N = off[-1]
+    row_len = [4096, 4096, 4096, 4096, 4096, 4096, 14336, 4096, 4096]       # the inner dimension of each tensor
+    row_sizes = [r for n, r in zip(sizes, row_len) for _ in range(n // r)]
+    row_off = synth.offsets_from_sizes(row_sizes)
+    assert row_off[-1] == N
+    theta = torch.empty(N, dtype=torch.float32, device=dev)
+    synth.fill_theta_outer(theta)
+    x = torch.empty(N, dtype=torch.float32, device=dev)
+    ws = B.new_workspace(len(row_sizes), dev)
+    rows = []
+
+    def measure(d, offsets, c, cb):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        codes, lut, _ = B.reduce_chunk([], [], offsets, 1, local_fp32=d, workspace=ws, variant=(c, cb))
+        e1.record()
+        val = ring.dequantise(codes, lut, offsets, workspace=ws)
+        err = float(torch.sqrt(torch.mean((val.double() - d.double()) ** 2)) / d.double().std())
+        clipped = float(((codes == 0) | (codes == 255)).float().mean())
+        return err, clipped, e0.elapsed_time(e1)
+
+    for kind in ("normal", "mixture", "student_t3"):
+        synth.fill_theta_local(x, theta, 0, kind)
+        d = (theta - x)
+        for c in (3.0, 4.0, 5.0, 6.0, 8.0, 10.0):
+            for cb, cbn in ((B.CODEBOOK_MEAN, "mean"), (B.CODEBOOK_MIDPOINT, "midpoint")):
+                err, clipped, ms = measure(d, off, c, cb)
+                rows.append({"delta": kind, "groups": "tensor", "range_sigmas": c, "codebook": cbn,
+                             "rms_error_over_std": round(err, 5), "end_bucket_fraction": round(clipped, 6)})
+                log(f"[study] {kind:10s} per tensor  c={c:4.1f} {cbn:8s}: rms error / std {err:.5f}  "
+                    f"end buckets {100 * clipped:.4f}%  ({ms:.2f} ms)")
+        for scaled in (False, True):
+            dd = d
+            if scaled:
+                g = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 77)
+                scale = torch.exp(torch.randn(len(row_sizes), device=dev, generator=g))
+                dd = d * torch.repeat_interleave(scale, torch.tensor(row_sizes, device=dev))
+            for groups, offsets in (("tensor", off), ("row", row_off)):
+                err, clipped, ms = measure(dd, offsets, 6.0, B.CODEBOOK_MEAN)
+                wire = 1.0 + 1024.0 * (len(offsets) - 1) / N
+                rows.append({"delta": kind + (" x log-normal row scales" if scaled else ""), "groups": groups,
+                             "range_sigmas": 6.0, "codebook": "mean", "rms_error_over_std": round(err, 5),
+                             "end_bucket_fraction": round(clipped, 6), "wire_bytes_per_element": round(wire, 4),
+                             "ms": round(ms, 3)})
+                log(f"[study] {kind:10s} rows scaled={scaled!s:5s} groups per {groups:6s}: rms error / std {err:.5f}  "
+                    f"wire {wire:.3f} B/elem  ({ms:.2f} ms, {len(offsets) - 1} groups)")
+            del dd
+    print(json.dumps({"study": "quantiser variants", "elements": N, "rows": rows}), flush=True)
 
 
 def measure_copy_kernel(torch, src_buf, dev):
