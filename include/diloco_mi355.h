@@ -48,6 +48,7 @@ extern "C" {
 
 #define DILOCO_MAX_PEERS 16u        /* largest W accepted by int8_reduce_chunk */
 #define DILOCO_MAX_SEGMENTS 65536u  /* largest T accepted */
+#define DILOCO_MAX_RING_NODES 20u   /* largest n accepted by diloco_ring_order */
 
 #define DILOCO_OK 0
 #define DILOCO_ERR_NULL (-1)        /* a required pointer is NULL                         */
@@ -196,6 +197,26 @@ int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* de
                             const uint64_t* seg_offsets, uint32_t T, uint64_t N, float lr,
                             float beta, void* theta_local_out, int32_t local_dtype,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Bandwidth-aware ring order (Section 2.5).  Given the measured bandwidth of every directed link,
+ * finds an order of the n nodes, closed into a ring, whose slowest link is as fast as possible:
+ * the Hamiltonian cycle C maximising min over its edges (u, v) of w(u, v).  Exact (threshold search
+ * over the edge weights with a subset recurrence for Hamiltonicity), host code only, no device use.
+ *
+ *   bandwidth       HOST, [n][n] row-major doubles; bandwidth[u * n + v] is the rate from node u to
+ *                   node v (any unit), finite and >= 0; the diagonal is ignored.  A symmetric
+ *                   matrix describes undirected links.
+ *   n               1 .. DILOCO_MAX_RING_NODES
+ *   order_out       HOST, [n]: the ring order[0] -> order[1] -> ... -> order[n-1] -> order[0];
+ *                   order[0] is node 0.  When several rings share the best bottleneck, any one of
+ *                   them is returned.
+ *   bottleneck_out  HOST, optional: the bandwidth of the slowest link of that ring (+infinity for n = 1)
+ * Returns DILOCO_OK, DILOCO_ERR_NULL, or DILOCO_ERR_SIZE (n out of range, a negative or non-finite
+ * bandwidth).
+ */
+int32_t diloco_ring_order(const double* bandwidth, uint32_t n, uint32_t* order_out,
+                          double* bottleneck_out);
 
 /*
  * Instrumentation for benchmarks (not part of the method).  After this call, every later call of

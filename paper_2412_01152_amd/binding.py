@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 import torch
@@ -30,7 +30,7 @@ assert QPARAMS_DTYPE.itemsize == QPARAMS_BYTES
 
 EXPORTS = ("diloco_workspace_bytes", "diloco_strerror", "diloco_pseudograd_quantize",
            "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes",
-           "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant")
+           "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant", "diloco_ring_order")
 
 CODEBOOK_MEAN, CODEBOOK_MIDPOINT = 0, 1
 
@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.diloco_pseudograd_quantize_variant.argtypes = lib.diloco_pseudograd_quantize.argtypes + [f64, u32]
     lib.int8_reduce_chunk_variant.restype = i32
     lib.int8_reduce_chunk_variant.argtypes = lib.int8_reduce_chunk.argtypes + [f64, u32]
+    lib.diloco_ring_order.restype = i32
+    lib.diloco_ring_order.argtypes = [vp, u32, vp, vp]
     lib.outer_nesterov_step.restype = i32
     lib.outer_nesterov_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u64, f32, f32, vp, i32, vp, sz, vp]
     lib.diloco_profile_passes.restype = i32
@@ -226,3 +228,19 @@ def outer_step(theta_outer: torch.Tensor, momentum: torch.Tensor, lr: float, bet
                                  _stream(stream))
     if rc != 0:
         raise DilocoError(rc, "outer_nesterov_step")
+
+
+def ring_order(bandwidth) -> Tuple[List[int], float]:
+    """diloco_ring_order: (order, bottleneck) for an [n][n] matrix of link bandwidths (host data)."""
+    lib = load()
+    w = np.ascontiguousarray(np.asarray(bandwidth, dtype=np.float64))
+    if w.ndim != 2 or w.shape[0] != w.shape[1]:
+        raise ValueError("bandwidth must be a square matrix")
+    n = w.shape[0]
+    order = np.zeros(max(n, 1), dtype=np.uint32)
+    bottleneck = ctypes.c_double(0.0)
+    rc = lib.diloco_ring_order(ctypes.c_void_p(w.ctypes.data), ctypes.c_uint32(n), ctypes.c_void_p(order.ctypes.data),
+                               ctypes.cast(ctypes.byref(bottleneck), ctypes.c_void_p))
+    if rc != 0:
+        raise DilocoError(rc, "diloco_ring_order")
+    return [int(v) for v in order[:n]], float(bottleneck.value)

@@ -27,7 +27,8 @@ UNITS = [("abi.o", "abi.hip", []),
          ("reduce_g0.o", "reduce_dispatch.hip", ["-DDILOCO_W_GROUP=0"]),
          ("reduce_g1.o", "reduce_dispatch.hip", ["-DDILOCO_W_GROUP=1"]),
          ("reduce_g2.o", "reduce_dispatch.hip", ["-DDILOCO_W_GROUP=2"]),
-         ("reduce_g3.o", "reduce_dispatch.hip", ["-DDILOCO_W_GROUP=3"])]
+         ("reduce_g3.o", "reduce_dispatch.hip", ["-DDILOCO_W_GROUP=3"]),
+         ("ring_order.o", "ring_order.cpp", [])]          # host code only
 
 
 EXTRA = os.environ.get("DILOCO_EXTRA_FLAGS", "").split()
