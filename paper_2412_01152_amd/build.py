@@ -10,8 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
-OUT = os.environ.get("DILOCO_OUT", os.path.join(HERE, "libdiloco_mi355.so"))
-BUILD = os.environ.get("DILOCO_BUILD_DIR", BUILD)
+OUT = os.path.join(HERE, "libdiloco_mi355.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -31,12 +30,9 @@ UNITS = [("abi.o", "abi.hip", []),
          ("ring_order.o", "ring_order.cpp", [])]          # host code only
 
 
-EXTRA = os.environ.get("DILOCO_EXTRA_FLAGS", "").split()
-
-
 def _compile(unit):
     obj, src, defs = unit
-    cmd = [HIPCC, *FLAGS, *EXTRA, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(BUILD, obj)]
+    cmd = [HIPCC, *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(BUILD, obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     return unit, r
 

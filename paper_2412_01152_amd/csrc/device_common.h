@@ -11,19 +11,12 @@ namespace diloco {
 
 constexpr int kThreads = 256;                       // 4 wave64 per block; also the number of buckets
 constexpr int kVec = 4;                             // consecutive elements per lane per load
-#ifndef DILOCO_UNROLL
-#define DILOCO_UNROLL 4
-#endif
-#ifndef DILOCO_COPIES_STREAM
-#define DILOCO_COPIES_STREAM 1      // bin copies in pass B of the memory-bound sources
-#endif
-#ifndef DILOCO_COPIES_REDUCE
-#define DILOCO_COPIES_REDUCE 16     // bin copies in pass B of the LDS-bound reduce source
-#endif
-#ifndef DILOCO_MIN_WAVES
-#define DILOCO_MIN_WAVES 1
-#endif
-constexpr int kUnroll = DILOCO_UNROLL;              // loads in flight per stream per lane
+constexpr int kUnroll = 4;                          // loads in flight per stream per lane
+// Copies of the 256 LDS bins in pass B (a lane uses copy lane % copies): one is enough where the
+// pass waits for two fp32 streams; the reduce source issues its atomics in denser bursts and runs
+// measurably faster with sixteen.
+constexpr int kBinCopiesStream = 1;
+constexpr int kBinCopiesReduce = 16;
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
 // Fixed-point bucket sums: a 64-bit LDS bin holds {count : 24 bits, sum of biased offsets : 40 bits}.
@@ -47,9 +40,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Every array here is streamed once per pass, so loads and stores carry the non-temporal hint
 // (measured on MI355X: about 12 % more read bandwidth than plain loads on a pure read stream).
-#ifndef DILOCO_NT
 #define DILOCO_NT 1
-#endif
 __device__ __forceinline__ f32x4 ld_f32x4(const float* p) {
 #if DILOCO_NT
     return __builtin_nontemporal_load((const f32x4_u*)p);

@@ -155,7 +155,7 @@ __global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t
 }
 
 template <class Src, bool kWriteAcc>
-__global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void stats_kernel(Src src_in, const uint64_t* __restrict__ seg,
+__global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, Work work,
                                                         double* __restrict__ stats,
                                                         const float* __restrict__ pivot,
@@ -318,7 +318,7 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
 // addresses, so that neighbouring lanes hit different banks even when they hit the same bucket
 // (a 64-bit bin spans two of the 32 banks; with 16 copies 16 consecutive lanes never collide).
 template <class Src, int kCopies>
-__global__ __launch_bounds__(kThreads, DILOCO_MIN_WAVES) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
+__global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, Work work,
                                                         const diloco_qparams* __restrict__ qp,
                                                         uint8_t* __restrict__ codes, PassBOut out) {

@@ -47,7 +47,7 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
 template <int W, bool kLocal, bool kTrueDiv>
 hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
-    constexpr auto kernel = quant_kernel<Src, DILOCO_COPIES_REDUCE>;
+    constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1));
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
