@@ -105,8 +105,9 @@ DILOCO_DECLARE_REDUCE_GROUP(2)
 DILOCO_DECLARE_REDUCE_GROUP(3)
 #undef DILOCO_DECLARE_REDUCE_GROUP
 
-// One contiguous share per block, no counter: the in-place outer step runs fastest as long walks
-// (measured: 28 ms with one share per block or 2M-element chunks, 32 ms with 128K-element chunks).
+// One contiguous share per block, no counter: the outer step needs no scratch this way (its fp32
+// form takes no workspace), and for this in-place kernel claimed chunks of any size from 32 K to
+// 2 M elements measured within 2 % of static shares when toggled inside one process.
 inline Grid plan_static(uint64_t N, int num_cus, int blocks_per_cu, uint32_t phase) {
     Grid g;
     uint64_t want = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
