@@ -147,6 +147,46 @@ def fill_theta_local(out: torch.Tensor, theta_outer: torch.Tensor, peer: int,
     return out
 
 
+def fill_delta(out: torch.Tensor, peer: int, kind: str = "mixture", seed: int = BASE_SEED) -> torch.Tensor:
+    """out[:] = a displacement drawn from the configuration's distribution (an fp32 pseudo-gradient
+    that is handed over as such: the chunk owner's un-quantised addend)."""
+    assert out.dtype == torch.float32 and out.dim() == 1
+    step = _chunk_elems(out.device)
+    for c, a in enumerate(range(0, out.numel(), step)):
+        b = min(a + step, out.numel())
+        out[a:b] = _delta_chunk(b - a, kind, out.device, _gen(out.device, seed, 1 + peer, c))
+    return out
+
+
+STREAM_CODES = 1000      # generator streams of the synthetic coded contributions: 1000 + peer
+
+
+def fill_coded_contribution(codes_out: torch.Tensor, peer: int, seed: int = BASE_SEED) -> torch.Tensor:
+    """Synthetic coded contribution for inputs too large to quantise on the host first: bytes with
+    the bell-shaped occupancy real codes have (a normal variate fills buckets 128 +- 21.3 per
+    standard deviation when the range is +-6 sigma in 256 buckets), clipped to 0..255."""
+    assert codes_out.dtype == torch.uint8 and codes_out.dim() == 1
+    step = _chunk_elems(codes_out.device)
+    for c, a in enumerate(range(0, codes_out.numel(), step)):
+        b = min(a + step, codes_out.numel())
+        g = _gen(codes_out.device, seed, STREAM_CODES + peer, c)
+        z = torch.randn(b - a, device=codes_out.device, generator=g)
+        codes_out[a:b] = (z * (256.0 / 12.0) + 128.0).floor_().clamp_(0, 255).to(torch.uint8)
+    return codes_out
+
+
+def synthetic_codebooks(groups: int, peer: int, std: float = 2.43e-3, device="cpu",
+                        seed: int = BASE_SEED) -> torch.Tensor:
+    """[groups][256] ascending fp32 codebooks to go with fill_coded_contribution: bucket centres of a
+    +-6 std range around a small per-group mean, each moved by up to a third of a bucket."""
+    g = _gen(device, seed, STREAM_CODES + peer, 1 << 20)
+    w = 12.0 * std / 256.0
+    k = torch.arange(256, device=device, dtype=torch.float32)
+    mean = torch.randn(groups, 1, device=device, generator=g) * (0.01 * std)
+    jitter = (torch.rand(groups, 256, device=device, generator=g) - 0.5) * (2.0 / 3.0)
+    return (mean + (k - 127.5 + jitter) * w).contiguous()
+
+
 def make_inputs(sizes: Sequence[int], peers: int, kind: str = "mixture", device="cpu",
                 seed: int = BASE_SEED, local_dtype=torch.float32):
     """Small-case helper: (theta_outer, [theta_local_p for p in range(peers)], seg_offsets)."""

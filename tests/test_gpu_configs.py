@@ -6,7 +6,9 @@ launch configuration and is checked on sampled tensors the oracle can process wh
 properties that hold at any size.  Configurations 3 and 4 keep their structure (14 heavy-tailed
 coded peers with the accumulation stored over theta_local; 14 ring chunks of a size that is not a
 multiple of anything, 13 coded peers + un-quantised local addend, bf16 theta_local) on the first
-attention block's tensors, a size the oracle finishes in seconds.
+attention block's tensors, a size the oracle finishes in seconds, and also run at full size: the
+reduce at W = 14 on all 381 tensors, checked on sampled tensors, and one whole ring chunk of
+729,384,375 elements at its odd offset inside full-size buffers.
 """
 import sys
 import time
@@ -272,3 +274,107 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
     g = lut2[0][codes2[a:b].long()]
     assert torch.equal(mom[a:b], g)
     say(f"[config2] stage 3 checked; total one-bucket flips on sampled tensors: {flips}")
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 3 at full size: 14 heavy-tailed coded peers resident (143 GB of codes), the
+# accumulation stored over theta_local, checked on sampled tensors
+# ---------------------------------------------------------------------------------------------
+
+def test_config3_fullsize_sampled_tensors(B, oracle_mod):
+    sizes = synth.config_segment_sizes(3)
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 14
+    free, _ = torch.cuda.mem_get_info()
+    if free < 245e9:
+        pytest.skip(f"needs about 240 GB of free HBM, have {free / 1e9:.0f} GB")
+    # final norm (4,096), layer 11 wv (4.2M), layer 30 wo (16.8M), layer 17 w_gate (58.7M)
+    sample = [T - 2, 1 + 9 * 11 + 2, 1 + 9 * 30 + 3, 1 + 9 * 17 + 4]
+    say(f"[config3] N={N} T={T} W={W}; sampled tensors {sample} sizes {[sizes[s] for s in sample]}")
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local = torch.empty(N, dtype=torch.float32, device=DEV)
+    peer_codes = [torch.empty(N, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=DEV) for _ in range(W)]
+    qp = B.new_qparams(T, DEV)
+    ws = B.new_workspace(T, DEV)
+    th_s = {s: t2n(theta[off[s]:off[s + 1]]) for s in sample}
+    o1 = {s: [] for s in sample}
+    t0 = time.time()
+    for p in range(W):
+        synth.fill_theta_local(local, theta, p, "student_t3")
+        B.pseudograd_quantize(theta, local, off, codes_out=peer_codes[p], lut_out=peer_luts[p], qparams_out=qp,
+                              workspace=ws)
+        torch.cuda.synchronize()
+        # the sampled tensors get the oracle's own stage-1 output (stage 2 is checked in isolation)
+        for s in sample:
+            a, b = off[s], off[s + 1]
+            o = oracle_mod.pseudograd_quantize(th_s[s], t2n(local[a:b]), [0, b - a])
+            o1[s].append(o)
+            peer_codes[p][a:b].copy_(torch.from_numpy(o[0]))
+            peer_luts[p][s].copy_(torch.from_numpy(o[1][0]))
+    say(f"[config3] {W} peers ready ({time.time() - t0:.1f}s)")
+    codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
+    lut2 = torch.empty((T, 256), dtype=torch.float32, device=DEV)
+    B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=local, codes_out=codes2, lut_out=lut2, qparams_out=qp,
+                   workspace=ws)
+    torch.cuda.synchronize()
+    g_qp = B.qparams_to_numpy(qp)
+    assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
+    flips = 0
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[0] for o in o1[s]], [o[1] for o in o1[s]], [0, b - a], W)
+        check_qparams(g_qp[s:s + 1], o_q2)
+        flips += check_codes(t2n(codes2[a:b]), o_c2, o_acc, [0, b - a], o_q2)
+        check_luts(t2n(lut2[s]), o_l2, o_c2, [0, b - a], o_q2)
+        assert np.array_equal(t2n(local[a:b]), o_acc)                 # a fixed sequence of fp32 operations
+    # any size: the requantised embedding tensor decodes to the same sum as the stored accumulation
+    a, b = off[0], off[1]
+    dec = lut2[0][codes2[a:b].long()].double()
+    acc = local[a:b].double()
+    assert abs(float(dec.sum() - acc.sum())) <= 2 ** -22 * float(acc.abs().sum())
+    say(f"[config3] stage 2 at W=14 checked on {len(sample)} tensors; one-bucket flips: {flips}")
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 4 at full size: one whole ring chunk (729,384,375 elements, starting at an odd
+# element offset of the full-size buffers), 13 coded contributions + the fp32 local addend
+# ---------------------------------------------------------------------------------------------
+
+def test_config4_fullsize_one_ring_chunk(B, oracle_mod):
+    N = synth.n_elements(2)
+    coff = synth.offsets_from_sizes(synth.ring_chunk_sizes(N, 14))
+    W, c = 13, 1
+    a, b = coff[c], coff[c + 1]
+    n = b - a
+    assert a % 2 == 1 and n == 729_384_375
+    free, _ = torch.cuda.mem_get_info()
+    if free < 190e9:
+        pytest.skip(f"needs about 185 GB of free HBM, have {free / 1e9:.0f} GB")
+    say(f"[config4] chunk {c}: elements [{a}, {b}) of {N}, W={W} coded + fp32 local")
+    # full-size buffers, as the benchmark holds them; only this chunk's part is filled
+    local = torch.empty(N, dtype=torch.float32, device=DEV)
+    peer_codes = [torch.empty(N, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
+    lut2 = torch.empty((14, 256), dtype=torch.float32, device=DEV)
+    synth.fill_delta(local[a:b], W, "mixture")
+    peer_luts = [synth.synthetic_codebooks(14, p, device=DEV) for p in range(W)]
+    for p in range(W):
+        synth.fill_coded_contribution(peer_codes[p][a:b], p)
+    torch.cuda.synchronize()
+    h_local = t2n(local[a:b])
+    h_codes = [t2n(pc[a:b]) for pc in peer_codes]
+    h_luts = [t2n(pl[c:c + 1]) for pl in peer_luts]
+    codes_g, lut_g, qp_g = B.reduce_chunk([pc[a:b] for pc in peer_codes], [pl[c:c + 1] for pl in peer_luts], [0, n], 14,
+                                          local_fp32=local[a:b], acc_out=local[a:b], codes_out=codes2[a:b],
+                                          lut_out=lut2[c:c + 1])
+    torch.cuda.synchronize()
+    t0 = time.time()
+    o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce(h_codes, h_luts, [0, n], 14, local_fp32=h_local)
+    say(f"[config4] oracle reduce of one chunk: {time.time() - t0:.1f}s")
+    del h_codes
+    check_qparams(B.qparams_to_numpy(qp_g), o_q2)
+    flips = check_codes(t2n(codes_g), o_c2, o_acc, [0, n], o_q2)
+    check_luts(t2n(lut_g), o_l2, o_c2, [0, n], o_q2)
+    assert np.array_equal(t2n(local[a:b]), o_acc)
+    say(f"[config4] one-bucket flips: {flips} of {n}")
