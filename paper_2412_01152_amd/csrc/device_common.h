@@ -19,6 +19,7 @@ constexpr int kBinCopiesStream = 1;
 constexpr int kBinCopiesReduce = 16;
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
+constexpr uint32_t kNoSegment = 0xffffffffu;
 // Fixed-point bucket sums: a 64-bit LDS bin holds {count : 24 bits, sum of biased offsets : 40 bits}.
 // An offset is at most one bucket width, scaled by 2^21 / width and biased by 2^22, so an addend is
 // below 2^23 and a bin takes 2^17 of them before the low field could carry into the count.
@@ -26,8 +27,10 @@ constexpr int kOffsetBits = 21;
 constexpr int kOffsetBias = 1 << 22;
 constexpr float kRoundMagic = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer
 constexpr int kCountShift = 40;
-constexpr int kFlushIters = 16;                     // 16 * kIter = 2^16 elements between drains
-// between two drains: kFlushIters iterations, one ragged tail (< kIter) and one head (< 128)
+constexpr int kFlushIters = 16;                     // the bins are drained once 2^16 elements are in
+// the count of binned elements is checked after every iteration and every ragged tail (< kIter
+// elements) and a head (< 128) may follow unchecked, so fewer than (kFlushIters + 2) * kIter
+// elements sit in the bins at any time
 static_assert((long long)(kFlushIters + 2) * kIter * (1ll << 23) <= (1ll << kCountShift), "bin overflow");
 
 // Vector types that promise only element alignment: gfx950 global memory instructions accept

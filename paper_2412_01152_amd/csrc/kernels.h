@@ -167,58 +167,72 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint6
     src.bind(s_src);
     const int tid = threadIdx.x;
     const uint32_t phase = work.phase;
+    // Sums stay in registers across the block's chunks for as long as the segment stays the same;
+    // they go to the segment's global accumulators when the segment changes and when the block
+    // leaves.  (With one quantisation group per ring chunk every block would otherwise send one
+    // pair of atomics per claim to the same two addresses.)
+    uint32_t cur = kNoSegment;
+    double c64 = 0.0, s1 = 0.0, s2 = 0.0;
+    auto flush_segment = [&]() {                 // block-uniform
+        block_sum2(s1, s2, s_red);
+        if (tid == 0) {
+            atomicAdd(&stats[2 * (size_t)cur], s1);
+            atomicAdd(&stats[2 * (size_t)cur + 1], s2);
+        }
+        s1 = 0.0;
+        s2 = 0.0;
+    };
     Claimer claimer(work);
     Share sh;
     while (claimer.claim(work, N, sh, &s_claim)) {
-    uint32_t s = find_segment(seg, T, sh.begin);
-    uint64_t pos = sh.begin;
-    while (pos < sh.end) {
-        const uint64_t seg_end = seg[s + 1];
-        if (seg_end <= pos) {
-            ++s;
-            continue;
-        }
-        const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
-        src.enter_segment(s);
-        const double c64 = (double)pivot[s];
-        double s1 = 0.0, s2 = 0.0;
-        auto single = [&](uint64_t lo, uint64_t hi) {
-            for (uint64_t i = lo + tid; i < hi; i += kThreads) {
-                float v = src.value1(i);
-                if (kWriteAcc) acc_out[i] = v;
-                double d = (double)v - c64;
-                s1 += d;
-                s2 = fma(d, d, s2);
+        uint32_t s = find_segment(seg, T, sh.begin);
+        uint64_t pos = sh.begin;
+        while (pos < sh.end) {
+            const uint64_t seg_end = seg[s + 1];
+            if (seg_end <= pos) {
+                ++s;
+                continue;
             }
-        };
-        uint64_t base = aligned_start(pos, sub_end, phase);
-        single(pos, base);
-        for (; base + kIter <= sub_end; base += kIter) {
-            typename Src::Raw raw[kUnroll];
-#pragma unroll
-            for (int j = 0; j < kUnroll; ++j)
-                raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
-#pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
-                f32x4 v = src.value4(raw[j]);
-                if (kWriteAcc) st_f32x4(acc_out + base + (uint64_t)(j * kThreads + tid) * kVec, v);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    double d = (double)v[e] - c64;
+            const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
+            if (s != cur) {
+                if (cur != kNoSegment) flush_segment();
+                cur = s;
+                src.enter_segment(s);
+                c64 = (double)pivot[s];
+            }
+            auto single = [&](uint64_t lo, uint64_t hi) {
+                for (uint64_t i = lo + tid; i < hi; i += kThreads) {
+                    float v = src.value1(i);
+                    if (kWriteAcc) acc_out[i] = v;
+                    double d = (double)v - c64;
                     s1 += d;
                     s2 = fma(d, d, s2);
                 }
+            };
+            uint64_t base = aligned_start(pos, sub_end, phase);
+            single(pos, base);
+            for (; base + kIter <= sub_end; base += kIter) {
+                typename Src::Raw raw[kUnroll];
+#pragma unroll
+                for (int j = 0; j < kUnroll; ++j)
+                    raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
+#pragma unroll
+                for (int j = 0; j < kUnroll; ++j) {
+                    f32x4 v = src.value4(raw[j]);
+                    if (kWriteAcc) st_f32x4(acc_out + base + (uint64_t)(j * kThreads + tid) * kVec, v);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        double d = (double)v[e] - c64;
+                        s1 += d;
+                        s2 = fma(d, d, s2);
+                    }
+                }
             }
+            single(base, sub_end);
+            pos = sub_end;
         }
-        single(base, sub_end);
-        block_sum2(s1, s2, s_red);
-        if (tid == 0) {
-            atomicAdd(&stats[2 * (size_t)s], s1);
-            atomicAdd(&stats[2 * (size_t)s + 1], s2);
-        }
-        pos = sub_end;
     }
-    }
+    if (cur != kNoSegment) flush_segment();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -331,89 +345,111 @@ __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint6
     const int tid = threadIdx.x;
     unsigned long long* const s_bin = s_bin_all + (tid & (kCopies - 1));   // this lane's copy
     const uint32_t phase = work.phase;
-    Claimer claimer(work);
-    Share sh;
-    while (claimer.claim(work, N, sh, &s_claim)) {
-    uint32_t s = find_segment(seg, T, sh.begin);
-    uint64_t pos = sh.begin;
-    while (pos < sh.end) {
-        const uint64_t seg_end = seg[s + 1];
-        if (seg_end <= pos) {
-            ++s;
-            continue;
+    // Bins and totals live across the block's chunks for as long as the segment stays the same: the
+    // LDS bins are drained into registers before their 40-bit field can overflow, and the registers
+    // go to the segment's global bins when the segment changes and when the block leaves.
+    uint32_t cur = kNoSegment;
+    BinScale bs = bin_scale(0.0f, 0.0f);
+    long long bin_q = 0;
+    unsigned long long bin_c = 0;
+    FarSums far;
+    uint32_t pending = 0;                        // elements binned since the last drain (block-uniform)
+    constexpr uint32_t kDrainAfter = (uint32_t)kFlushIters * kIter;
+#pragma unroll
+    for (int c = 0; c < kCopies; ++c) s_bin_all[c * kBuckets + tid] = 0;
+    __syncthreads();
+    // thread k sums and clears the kCopies copies of bin k, starting at a rotated copy so that the
+    // lanes of a wave read different banks; callers put a barrier before and after
+    auto drain = [&]() {
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) {
+            const int idx = tid * kCopies + ((i + tid) & (kCopies - 1));
+            const unsigned long long packed = s_bin_all[idx];
+            s_bin_all[idx] = 0;
+            const unsigned long long c = packed >> kCountShift;
+            bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kOffsetBias;
+            bin_c += c;
         }
-        const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
-        src.enter_segment(s);
-        const BinScale bs = bin_scale(qp[s].lo, qp[s].inv_w);
-        long long bin_q = 0;
-        unsigned long long bin_c = 0;
-        FarSums far;
-#pragma unroll
-        for (int c = 0; c < kCopies; ++c) s_bin_all[c * kBuckets + tid] = 0;
+        pending = 0;
+    };
+    auto flush_segment = [&]() {                 // block-uniform
         __syncthreads();
-        // thread k sums (and clears) the kCopies copies of bin k, starting at a rotated copy so
-        // that the lanes of a wave read different banks
-        auto drain = [&](bool clear) {
-#pragma unroll
-            for (int i = 0; i < kCopies; ++i) {
-                const int idx = tid * kCopies + ((i + tid) & (kCopies - 1));
-                const unsigned long long packed = s_bin_all[idx];
-                if (clear) s_bin_all[idx] = 0;
-                const unsigned long long c = packed >> kCountShift;
-                bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kOffsetBias;
-                bin_c += c;
-            }
-        };
-        auto single = [&](uint64_t lo, uint64_t hi) {
-            for (uint64_t i = lo + tid; i < hi; i += kThreads)
-                codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far);
-        };
-        uint64_t base = aligned_start(pos, sub_end, phase);
-        single(pos, base);
-        int since_flush = 0;
-        for (; base + kIter <= sub_end; base += kIter) {
-            typename Src::Raw raw[kUnroll];
-#pragma unroll
-            for (int j = 0; j < kUnroll; ++j)
-                raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
-#pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
-                const f32x4 v = src.value4(raw[j]);
-                st_u8x4(codes + base + (uint64_t)(j * kThreads + tid) * kVec,
-                        code_and_bin4(v, bs, s_bin, kCopies, far));
-            }
-            if (++since_flush == kFlushIters) {
-                since_flush = 0;
-                __syncthreads();
-                drain(true);
-                __syncthreads();
-            }
-        }
-        single(base, sub_end);
-        __syncthreads();
-        drain(false);
+        drain();
         if (bin_c) {
-            atomicAdd(&out.hsumq[(size_t)s * kBuckets + tid], (unsigned long long)bin_q);
-            atomicAdd(&out.hcnt[(size_t)s * kBuckets + tid], bin_c);
+            atomicAdd(&out.hsumq[(size_t)cur * kBuckets + tid], (unsigned long long)bin_q);
+            atomicAdd(&out.hcnt[(size_t)cur * kBuckets + tid], bin_c);
         }
-        if (__syncthreads_or((int)(far.lo_cnt | far.hi_cnt))) {
+        bin_q = 0;
+        bin_c = 0;
+        if (__syncthreads_or((int)(far.lo_cnt | far.hi_cnt))) {      // also the barrier after the drain
             double c_lo = (double)far.lo_cnt, c_hi = (double)far.hi_cnt;
             block_sum2(far.lo_sum, far.hi_sum, s_red);
             block_sum2(c_lo, c_hi, s_red);
             if (tid == 0) {
                 if (c_lo > 0.0) {
-                    atomicAdd(&out.osum[2 * (size_t)s], far.lo_sum);
-                    atomicAdd(&out.ocnt[2 * (size_t)s], (unsigned long long)c_lo);
+                    atomicAdd(&out.osum[2 * (size_t)cur], far.lo_sum);
+                    atomicAdd(&out.ocnt[2 * (size_t)cur], (unsigned long long)c_lo);
                 }
                 if (c_hi > 0.0) {
-                    atomicAdd(&out.osum[2 * (size_t)s + 1], far.hi_sum);
-                    atomicAdd(&out.ocnt[2 * (size_t)s + 1], (unsigned long long)c_hi);
+                    atomicAdd(&out.osum[2 * (size_t)cur + 1], far.hi_sum);
+                    atomicAdd(&out.ocnt[2 * (size_t)cur + 1], (unsigned long long)c_hi);
                 }
             }
+            far = FarSums();
         }
-        pos = sub_end;
+    };
+    Claimer claimer(work);
+    Share sh;
+    while (claimer.claim(work, N, sh, &s_claim)) {
+        uint32_t s = find_segment(seg, T, sh.begin);
+        uint64_t pos = sh.begin;
+        while (pos < sh.end) {
+            const uint64_t seg_end = seg[s + 1];
+            if (seg_end <= pos) {
+                ++s;
+                continue;
+            }
+            const uint64_t sub_end = seg_end < sh.end ? seg_end : sh.end;
+            if (s != cur) {
+                if (cur != kNoSegment) flush_segment();
+                cur = s;
+                src.enter_segment(s);
+                bs = bin_scale(qp[s].lo, qp[s].inv_w);
+            }
+            auto single = [&](uint64_t lo, uint64_t hi) {
+                for (uint64_t i = lo + tid; i < hi; i += kThreads)
+                    codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far);
+                pending += (uint32_t)(hi - lo);
+            };
+            auto drain_if_due = [&]() {
+                if (pending >= kDrainAfter) {
+                    __syncthreads();
+                    drain();
+                    __syncthreads();
+                }
+            };
+            uint64_t base = aligned_start(pos, sub_end, phase);
+            single(pos, base);                   // fewer than 128 elements
+            for (; base + kIter <= sub_end; base += kIter) {
+                typename Src::Raw raw[kUnroll];
+#pragma unroll
+                for (int j = 0; j < kUnroll; ++j)
+                    raw[j] = src.fetch4(base + (uint64_t)(j * kThreads + tid) * kVec);
+#pragma unroll
+                for (int j = 0; j < kUnroll; ++j) {
+                    const f32x4 v = src.value4(raw[j]);
+                    st_u8x4(codes + base + (uint64_t)(j * kThreads + tid) * kVec,
+                            code_and_bin4(v, bs, s_bin, kCopies, far));
+                }
+                pending += kIter;
+                drain_if_due();
+            }
+            single(base, sub_end);               // fewer than kIter elements
+            drain_if_due();
+            pos = sub_end;
+        }
     }
-    }
+    if (cur != kNoSegment) flush_segment();
 }
 
 }  // namespace diloco
