@@ -58,15 +58,27 @@ inline int resident_blocks_per_cu() {
 }
 
 // Launch shape of a streaming pass: all blocks resident (grid = CUs x resident blocks, fewer when
-// the buffer is small), chunks of at most 32 block iterations claimed dynamically, at least about
-// 16 chunks per block when the buffer is small so that the claiming can still balance the load.
+// the buffer is small), chunks of at most max_chunk_iters block iterations claimed dynamically, at
+// least about 16 chunks per block when the buffer is small so that the claiming can still balance
+// the load.
 struct Grid {
     uint32_t blocks;
     Work work;
 };
-// 32 iterations = 131,072 elements per claim: a claim costs about 22 ns at the counter, so chunks
-// below 8 iterations make the counter the bottleneck, and chunks much above 32 bring the tail back.
-constexpr uint64_t kMaxChunkIters = 32;
+// Elements per claim, in block iterations of 4,096 elements (upper limits; small buffers get
+// smaller chunks so that every block still sees about 16 of them).  A claim costs about 20 ns at
+// the one counter, which bounds how short a chunk may be: a pass that moves 5 bytes per element takes
+// 8.5 ms at 8 iterations and 10.5 ms at 4, one that moves 20 and more is still faster at 4.  Measured inside
+// one process at the 10B size: passes that only read run fastest with long chunks (stage 1 pass A:
+// 12.12 ms at 32, 11.73 ms at 128), passes that also write with short ones, which keep the blocks'
+// working set within a narrower window of addresses (stage 1 pass B: 15.32 ms at 32, 14.94 ms at 8;
+// bf16: 12.99 -> 12.42 ms; pass A of the reduce when it stores the accumulation, W = 14: 33.4 ms at
+// 32, 32.0 ms at 4).  Pass B of the reduce source recomputing from W code streams is the exception
+// at small W (W = 4: 9.66 ms at 64, 9.93 ms at 8; W = 8: 16.6 against 16.1 ms).
+constexpr uint64_t kChunkItersRead = 128;
+constexpr uint64_t kChunkItersWrite = 8;
+constexpr uint64_t kChunkItersStoreAcc = 4;
+inline uint64_t chunk_iters_reduce_write(uint32_t W) { return W <= 4 ? 64 : 16; }
 inline uint32_t host_phase(const void* p, int elem_bytes) {
     return (uint32_t)((uintptr_t)p / (uintptr_t)elem_bytes) & (kAlignElems - 1);
 }
@@ -77,14 +89,15 @@ inline void set_phase(Work& w, uint64_t N, uint32_t phase) {
     w.num_chunks = (body + w.chunk - 1) / w.chunk;
     if (w.num_chunks < 1) w.num_chunks = 1;
 }
-inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long long* counter, uint32_t phase) {
+inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long long* counter, uint32_t phase,
+                      uint64_t max_chunk_iters) {
     Grid g;
     const uint64_t resident = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
     uint64_t iters = (N + kIter - 1) / kIter;
     if (iters < 1) iters = 1;
     uint64_t chunk_iters = iters / (resident * 16);
     if (chunk_iters < 1) chunk_iters = 1;
-    if (chunk_iters > kMaxChunkIters) chunk_iters = kMaxChunkIters;
+    if (chunk_iters > max_chunk_iters) chunk_iters = max_chunk_iters;
     g.work.counter = counter;
     g.work.chunk = chunk_iters * kIter;
     set_phase(g.work, N, phase);

@@ -35,7 +35,8 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     constexpr auto kernel = stats_kernel<Src, kWriteAcc>;
     const uint32_t phase = acc_out ? host_phase(acc_out, 4)
                                    : (W > 0 ? host_phase(a.codes[0], 1) : host_phase(a.local, 4));
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0, phase);
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0, phase,
+                       kWriteAcc ? kChunkItersStoreAcc : kChunkItersRead);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.work, p.stats, p.pivot, acc_out);
@@ -48,7 +49,8 @@ template <int W, bool kLocal, bool kTrueDiv>
 hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
     constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1));
+    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
+                       chunk_iters_reduce_write(W));
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
