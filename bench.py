@@ -645,9 +645,10 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
           lambda: B.reduce_chunk(peer_codes[1:], peer_luts[1:], off, W, local_fp32=local, acc_out=local,
                                  codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws))
     timed("stage3 fp32 delta (20 B/elem)", 20,
-          lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local))
+          lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local, workspace=ws))
     timed("stage3 fp32 delta + fp32 hand-back (24 B/elem)", 24,
-          lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local, theta_local_out=codes_as_f32(torch, codes1, codes2, N)))
+          lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local, workspace=ws,
+                               theta_local_out=codes_as_f32(torch, codes1, codes2, N)))
     return out
 
 

@@ -170,23 +170,38 @@ hipError_t reduce_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams
         if (e_ != hipSuccess) return (int32_t)e_;    \
     } while (0)
 
+// counter == nullptr: one contiguous share per block; otherwise chunks claimed from the counter
+// (zeroed here, on the stream).
 template <int kOut>
 hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t* codes, const float* lut,
                      const uint64_t* seg, uint32_t T, uint64_t N, float lr, float beta, void* local_out,
-                     int num_cus, hipStream_t stream) {
-    (void)mark(0, stream);
+                     int num_cus, unsigned long long* counter, hipStream_t stream) {
+    if (counter) {
+        hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(64), 0, stream, (uint64_t*)counter, (size_t)1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const uint32_t phase = host_phase(theta, 4);
+    hipError_t e;
     if (delta) {
         constexpr auto kernel = outer_fp32_kernel<kOut>;
-        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>(), host_phase(theta, 4));
+        const int bpc = resident_blocks_per_cu<kernel>();
+        Grid g = counter ? plan_grid(N, num_cus, bpc, counter, phase, kChunkItersOuter)
+                         : plan_static(N, num_cus, bpc, phase);
+        (void)mark(0, stream);
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, delta, N,
                            g.work, lr, beta, local_out);
+        e = hipGetLastError();
     } else {
         constexpr auto kernel = outer_coded_kernel<kOut>;
-        Grid g = plan_static(N, num_cus, resident_blocks_per_cu<kernel>(), host_phase(theta, 4));
+        const int bpc = resident_blocks_per_cu<kernel>();
+        Grid g = counter ? plan_grid(N, num_cus, bpc, counter, phase, kChunkItersOuter)
+                         : plan_static(N, num_cus, bpc, phase);
+        (void)mark(0, stream);
         hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, stream, theta, mom, codes, lut, seg, T,
                            N, g.work, lr, beta, local_out);
+        e = hipGetLastError();
     }
-    hipError_t e = hipGetLastError();
     (void)mark(1, stream);
     return e;
 }
@@ -356,6 +371,7 @@ int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* de
         misaligned(theta_local_out, local_dtype == DILOCO_DTYPE_BF16 ? 2 : 4))
         return DILOCO_ERR_ALIGN;
     const uint64_t* seg_dev = nullptr;
+    unsigned long long* counter = nullptr;
     if (coded) {
         int32_t rc = check_segments(seg_offsets, T, N);
         if (rc) return rc;
@@ -366,6 +382,14 @@ int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* de
         if (N == 0) return DILOCO_OK;
         DILOCO_TRY(upload_offsets(seg_offsets, T + 1, (uint64_t*)((char*)workspace + L.seg), stream));
         seg_dev = (const uint64_t*)((char*)workspace + L.seg);
+        counter = (unsigned long long*)((char*)workspace + L.counters) + 2;
+    } else if (workspace) {
+        // optional for the fp32 form: with a workspace the blocks claim chunks, without one each
+        // block walks one static share
+        if (misaligned(workspace, 256)) return DILOCO_ERR_ALIGN;
+        const WorkspaceLayout L = workspace_layout(1);
+        if (workspace_bytes < L.total) return DILOCO_ERR_WORKSPACE;
+        counter = (unsigned long long*)((char*)workspace + L.counters) + 2;
     }
     if (N == 0) return DILOCO_OK;
     int cus = 0;
@@ -375,15 +399,15 @@ int32_t outer_nesterov_step(float* theta_outer, float* momentum, const float* de
     switch (out) {
         case kOutNone:
             DILOCO_TRY(run_outer<kOutNone>(theta_outer, momentum, delta_fp32, delta_codes, delta_lut, seg_dev,
-                                           T, N, lr, beta, theta_local_out, cus, stream));
+                                           T, N, lr, beta, theta_local_out, cus, counter, stream));
             break;
         case kOutF32:
             DILOCO_TRY(run_outer<kOutF32>(theta_outer, momentum, delta_fp32, delta_codes, delta_lut, seg_dev,
-                                          T, N, lr, beta, theta_local_out, cus, stream));
+                                          T, N, lr, beta, theta_local_out, cus, counter, stream));
             break;
         default:
             DILOCO_TRY(run_outer<kOutBf16>(theta_outer, momentum, delta_fp32, delta_codes, delta_lut, seg_dev,
-                                           T, N, lr, beta, theta_local_out, cus, stream));
+                                           T, N, lr, beta, theta_local_out, cus, counter, stream));
             break;
     }
     return DILOCO_OK;

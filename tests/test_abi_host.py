@@ -101,6 +101,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert o(fake, fake, fake, fake, fake, sp, 1, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -1
     assert o(fake, fake, vp(0), fake, vp(0), sp, 1, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -1
     assert o(fake, fake, vp(0), fake, fake, sp, 1, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -1   # no workspace
+    # the fp32 form takes an optional workspace: if given it must be aligned and large enough
+    assert o(fake, fake, fake, vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), vp(0), 0, vp(0x1010), 1 << 20, vp(0)) == -3
+    assert o(fake, fake, fake, vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), vp(0), 0, fake, 8, vp(0)) == -4
     assert o(fake, fake, fake, vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), fake, 9, vp(0), 0, vp(0)) == -5
     assert o(vp(0x1001), fake, fake, vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -3
 

@@ -259,9 +259,12 @@ def test_stage2_misaligned_chunk(B, oracle_mod):
 # stage 3
 # ---------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("coded", [False, True])
+@pytest.mark.parametrize("coded", [False, True, "fp32 with workspace"])
 @pytest.mark.parametrize("out", [None, torch.float32, torch.bfloat16])
 def test_stage3_outer_step(B, oracle_mod, coded, out):
+    # the fp32 form walks static shares without a workspace and claims chunks with one
+    ws = B.new_workspace(1, DEV) if coded == "fp32 with workspace" else None
+    coded = coded is True
     sizes = [100_000, 4097, 1, 250_000]
     n = sum(sizes)
     off = synth.offsets_from_sizes(sizes)
@@ -285,7 +288,8 @@ def test_stage3_outer_step(B, oracle_mod, coded, out):
                                                            torch.bfloat16: "bf16"}[out])
             gg = np.concatenate([o_luts[s][o_codes[off[s]:off[s + 1]]] for s in range(len(sizes))])
         else:
-            B.outer_step(th_t, m_t, lr, beta, delta_fp32=torch.from_numpy(g).to(DEV), theta_local_out=out_t)
+            B.outer_step(th_t, m_t, lr, beta, delta_fp32=torch.from_numpy(g).to(DEV), theta_local_out=out_t,
+                         workspace=ws)
             o_out = oracle_mod.outer_step(th_o, m_o, lr, beta, delta_fp32=g,
                                           local_out_dtype={None: None, torch.float32: "fp32",
                                                            torch.bfloat16: "bf16"}[out])
