@@ -65,6 +65,9 @@ def main():
                     help="quantiser: error of the 8-bit code for other clipping widths, the midpoint codebook and "
                          "per-row groups, on one decoder layer; ring: error and time of the per-hop ring reduce (requantised at every hop) against the "
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
+    ap.add_argument("--no-arena", action="store_true",
+                    help="allocate every buffer separately instead of carving them from one arena whose "
+                         "placement is chosen by timing the outer step (config 2 only)")
     ap.add_argument("--cpu-layers", type=int, default=4,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
@@ -101,14 +104,33 @@ def main():
     log(f"[bench] config {cfg}: N={N} T={T} W={W}; allocating")
 
     t0 = time.time()
-    theta = torch.empty(N, dtype=torch.float32, device=dev)
-    local = torch.empty(N, dtype=torch.float32, device=dev)
-    mom = torch.zeros(N, dtype=torch.float32, device=dev)
-    peer_codes = [torch.empty(N, dtype=torch.uint8, device=dev) for _ in range(W)]
+    # All large buffers come out of one allocation made before anything else, in the order theta,
+    # theta_local, momentum, peer codes, codes of stage 1, codes of stage 2: their physical placement
+    # is then the same in every process (see paper_2412_01152_amd/arena.py), and the shift of the whole
+    # group inside the arena is chosen by timing the outer step on a few candidates (setup, untimed).
+    arena = None
+    if cfg == 2 and not args.no_arena:
+        from paper_2412_01152_amd.arena import Arena, place_outer_state
+        arena = Arena(dev)
+        shift = place_outer_state(arena, N, off, range(0, 41, 5), tail_bytes=(W + 2) * N, log=log)
+        log(f"[bench] arena of {arena.nbytes >> 30} GiB, state carved at +{shift >> 30} GiB")
+
+    def alloc(numel, dtype, at=None):
+        if arena is not None:
+            try:
+                return arena.carve(numel, dtype, at=at)
+            except RuntimeError:
+                pass
+        return torch.empty(numel, dtype=dtype, device=dev)
+
+    theta = alloc(N, torch.float32, at=shift if arena is not None else None)
+    local = alloc(N, torch.float32)
+    mom = alloc(N, torch.float32).zero_()
+    peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
     peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=dev) for _ in range(W)]
-    codes1 = torch.empty(N, dtype=torch.uint8, device=dev)
+    codes1 = alloc(N, torch.uint8)
     lut1 = torch.empty((T, 256), dtype=torch.float32, device=dev)
-    codes2 = torch.empty(N, dtype=torch.uint8, device=dev)
+    codes2 = alloc(N, torch.uint8)
     lut2 = torch.empty((T, 256), dtype=torch.float32, device=dev)
     qp = B.new_qparams(T, dev)
     ws = B.new_workspace(T, dev)
@@ -125,7 +147,7 @@ def main():
     # ---- CPU oracle on a bounded sample, before theta is modified (baseline only) -------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
-        cpu_baseline = cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, args.cpu_layers)
+        cpu_baseline = cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, args.cpu_layers, alloc)
 
     def step(events=None):
         if events is not None:
@@ -214,13 +236,13 @@ def main():
                      "GB/s": round(STAGE_BYTES[s] * N / (avg * 1e-3) / 1e9, 1),
                      "frac_of_peak": round(STAGE_BYTES[s] * N / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         log(f"[bench] {s}: {avg:.3f} ms  {stages[s]['GB/s']:.1f} GB/s ({100 * stages[s]['GB/s'] / HBM_PEAK_GBS:.1f}%)")
-    copy_ref = measure_copy_kernel(torch, local, dev)
+    copy_ref = measure_copy_kernel(torch, local, alloc)
     log(f"[bench] plain copy kernel ({copy_ref['what']}): {copy_ref['GB/s']:.1f} GB/s; "
         f"step runs at {100 * value / copy_ref['GB/s']:.1f}% of it")
     extras = None
     if args.extras:
         extras = time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws,
-                             off, N, T, W)
+                             off, N, T, W, alloc)
     dominant = max(names, key=lambda n: kernels[n]["avg_ms"])
     achieved = kernels[dominant]["GB/s"]
     traffic = measured_traffic_bytes(dominant) if cfg == 2 else None
@@ -355,13 +377,13 @@ def study_quantiser(args, np, torch, B, synth, dev):
     print(json.dumps({"study": "quantiser variants", "elements": N, "rows": rows}), flush=True)
 
 
-def measure_copy_kernel(torch, src_buf, dev):
+def measure_copy_kernel(torch, src_buf, alloc):
     """Bandwidth of a plain elementwise copy (read 4 B, write 4 B per element) of 2^30 fp32, measured
     in this process: the nominal 8 TB/s is never reached by any kernel, so the step is also
     reported as a fraction of this."""
     n = 1 << 30
     src = src_buf[:n]
-    dst = torch.empty(n, dtype=torch.float32, device=dev)
+    dst = alloc(n, torch.float32)
     best = 0.0
     for name, fn in (("elementwise x*2 over 2^30 fp32", lambda: torch.mul(src, 2.0, out=dst)),
                      ("tensor copy 2^30 fp32", lambda: dst.copy_(src))):
@@ -610,7 +632,8 @@ def bench_config4_overlap(args, np, torch, B, synth, dev):
     print(json.dumps(result), flush=True)
 
 
-def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws, off, N, T, W):
+def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws, off, N, T, W,
+                alloc):
     """Whole-call timings (HIP events around the call, 5 repetitions) of the variants bench's step does
     not use.  Runs last: the stored-accumulation variant overwrites theta_local."""
     out = {}
@@ -630,7 +653,8 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
                      "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
         log(f"[bench] extra {name:52s} {ms:8.3f} ms  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:.1f}% of peak")
 
-    local_bf16 = local.to(torch.bfloat16)
+    local_bf16 = alloc(N, torch.bfloat16).copy_(local)
+    scratch_f32 = alloc(N, torch.float32)
     timed("stage1 bf16 theta_local (13 B/elem)", 13,
           lambda: B.pseudograd_quantize(theta, local_bf16, off, codes_out=codes1, lut_out=lut1, qparams_out=qp,
                                         workspace=ws))
@@ -648,18 +672,8 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
           lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local, workspace=ws))
     timed("stage3 fp32 delta + fp32 hand-back (24 B/elem)", 24,
           lambda: B.outer_step(theta, mom, LR, BETA, delta_fp32=local, workspace=ws,
-                               theta_local_out=codes_as_f32(torch, codes1, codes2, N)))
+                               theta_local_out=scratch_f32))
     return out
-
-
-def codes_as_f32(torch, codes1, codes2, N):
-    """A throw-away fp32 [N] destination for the hand-back timing, if one fits in free memory."""
-    global _SCRATCH_F32
-    try:
-        return _SCRATCH_F32
-    except NameError:
-        _SCRATCH_F32 = torch.empty(N, dtype=torch.float32, device=codes1.device)
-        return _SCRATCH_F32
 
 
 def measured_traffic_bytes(kernel_name):
@@ -680,7 +694,7 @@ def measured_traffic_bytes(kernel_name):
     return None
 
 
-def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, layers):
+def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, layers, alloc):
     """Times the oracle's three stages on the first decoder layers of the same workload
     (9 tensors, 218,112,000 elements per layer), copied down from the device."""
     import oracle
@@ -698,7 +712,7 @@ def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, laye
     # contributions of the other peers: the oracle makes its own codes from freshly generated
     # theta_local slices (setup, untimed); nothing the GPU library produced is used
     pcs, pls = [], []
-    scratch = torch.empty(n, dtype=torch.float32, device=theta.device)
+    scratch = alloc(n, torch.float32)
     threads = oracle.num_threads()
     t_setup = time.perf_counter()
     for p in range(1, W):
