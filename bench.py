@@ -67,7 +67,7 @@ def main():
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
     ap.add_argument("--no-arena", action="store_true",
                     help="allocate every buffer separately instead of carving them from one arena whose "
-                         "placement is chosen by timing the outer step (config 2 only)")
+                         "placement is chosen by timing the outer step (configs 2, 3 and 4)")
     ap.add_argument("--cpu-layers", type=int, default=4,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
@@ -401,6 +401,17 @@ def measure_copy_kernel(torch, src_buf, alloc):
     return {"GB/s": round(best, 1), "what": what}
 
 
+def arena_alloc(args, torch, dev):
+    """alloc(numel, dtype): views carved in call order from one arena (reproducible placement), or
+    separate allocations with --no-arena."""
+    if args.no_arena:
+        return lambda numel, dtype: torch.empty(numel, dtype=dtype, device=dev)
+    from paper_2412_01152_amd.arena import Arena
+    arena = Arena(dev)
+    log(f"[bench] arena of {arena.nbytes >> 30} GiB")
+    return arena.carve
+
+
 def bench_config3(args, np, torch, B, synth, dev):
     """Configuration 3: the reduce step alone at W = 14 heavy-tailed coded peers on the full 10B set
     (143 GB of codes resident), accumulation stored over theta_local (no room for a fourth fp32 array
@@ -410,11 +421,12 @@ def bench_config3(args, np, torch, B, synth, dev):
     N, T, W = off[-1], len(sizes), 14
     log(f"[bench] config 3: N={N} T={T} W={W}; allocating {(W + 1) * N / 1e9 + 8 * N / 1e9:.0f} GB")
     t0 = time.time()
-    theta = torch.empty(N, dtype=torch.float32, device=dev)
-    local = torch.empty(N, dtype=torch.float32, device=dev)
-    peer_codes = [torch.empty(N, dtype=torch.uint8, device=dev) for _ in range(W)]
+    alloc = arena_alloc(args, torch, dev)
+    theta = alloc(N, torch.float32)
+    local = alloc(N, torch.float32)
+    peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
     peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=dev) for _ in range(W)]
-    codes2 = torch.empty(N, dtype=torch.uint8, device=dev)
+    codes2 = alloc(N, torch.uint8)
     lut2 = torch.empty((T, 256), dtype=torch.float32, device=dev)
     qp = B.new_qparams(T, dev)
     ws = B.new_workspace(T, dev)
@@ -485,11 +497,12 @@ def bench_config4(args, np, torch, B, synth, dev):
     W = 13
     log(f"[bench] config 4: N={N}, 14 chunks of {chunk_sizes[0]} (last {chunk_sizes[-1]}), W={W} coded + local")
     t0 = time.time()
-    theta = torch.empty(N, dtype=torch.float32, device=dev)
-    local = torch.empty(N, dtype=torch.float32, device=dev)
-    peer_codes = [torch.empty(N, dtype=torch.uint8, device=dev) for _ in range(W)]
+    alloc = arena_alloc(args, torch, dev)
+    theta = alloc(N, torch.float32)
+    local = alloc(N, torch.float32)
+    peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
     peer_luts = [torch.empty((14, 256), dtype=torch.float32, device=dev) for _ in range(W)]
-    codes2 = torch.empty(N, dtype=torch.uint8, device=dev)
+    codes2 = alloc(N, torch.uint8)
     lut2 = torch.empty((14, 256), dtype=torch.float32, device=dev)
     qp = B.new_qparams(14, dev)
     ws = B.new_workspace(14, dev)
