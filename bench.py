@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--no-arena", action="store_true",
                     help="allocate every buffer separately instead of carving them from one arena whose "
                          "placement is chosen by timing the outer step (configs 2, 3 and 4)")
+    ap.add_argument("--arena-shift", type=int, default=None, metavar="GIB",
+                    help="config 2: carve the state at this shift of the arena instead of timing the outer step "
+                         "on the candidates (profiling runs: keeps the probes out of the kernel statistics)")
     ap.add_argument("--cpu-layers", type=int, default=4,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
@@ -112,7 +115,10 @@ def main():
     if cfg == 2 and not args.no_arena:
         from paper_2412_01152_amd.arena import Arena, place_outer_state
         arena = Arena(dev)
-        shift = place_outer_state(arena, N, off, range(0, 41, 5), tail_bytes=(W + 2) * N, log=log)
+        if args.arena_shift is not None:
+            shift = args.arena_shift << 30
+        else:
+            shift = place_outer_state(arena, N, off, range(0, 41, 5), tail_bytes=(W + 2) * N, log=log)
         log(f"[bench] arena of {arena.nbytes >> 30} GiB, state carved at +{shift >> 30} GiB")
 
     def alloc(numel, dtype, at=None):
