@@ -114,11 +114,22 @@ def main():
     arena = None
     if cfg == 2 and not args.no_arena:
         from paper_2412_01152_amd.arena import Arena, place_outer_state
-        arena = Arena(dev)
+        need = (12 + W + 2) * N + (1 << 30)
+        try:
+            arena = Arena(dev)
+            if arena.nbytes < need:
+                raise RuntimeError(f"arena of {arena.nbytes >> 30} GiB is too small")
+        except RuntimeError as e:                 # e.g. another process holds part of the HBM
+            log(f"[bench] no arena ({e}); falling back to one allocation per buffer")
+            arena = None
+            torch.cuda.empty_cache()
+    if arena is not None:
         if args.arena_shift is not None:
             shift = args.arena_shift << 30
         else:
             shift = place_outer_state(arena, N, off, range(0, 41, 5), tail_bytes=(W + 2) * N, log=log)
+        if shift + need > arena.nbytes:
+            shift = 0
         log(f"[bench] arena of {arena.nbytes >> 30} GiB, state carved at +{shift >> 30} GiB")
 
     def alloc(numel, dtype, at=None):
@@ -413,9 +424,19 @@ def arena_alloc(args, torch, dev):
     if args.no_arena:
         return lambda numel, dtype: torch.empty(numel, dtype=dtype, device=dev)
     from paper_2412_01152_amd.arena import Arena
-    arena = Arena(dev)
+    try:
+        arena = Arena(dev)
+    except RuntimeError as e:
+        log(f"[bench] no arena ({e}); falling back to one allocation per buffer")
+        return lambda numel, dtype: torch.empty(numel, dtype=dtype, device=dev)
     log(f"[bench] arena of {arena.nbytes >> 30} GiB")
-    return arena.carve
+
+    def carve(numel, dtype):
+        try:
+            return arena.carve(numel, dtype)
+        except RuntimeError:
+            return torch.empty(numel, dtype=dtype, device=dev)
+    return carve
 
 
 def bench_config3(args, np, torch, B, synth, dev):
