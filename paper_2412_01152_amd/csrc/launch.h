@@ -58,9 +58,7 @@ inline int resident_blocks_per_cu() {
 }
 
 // Launch shape of a streaming pass: all blocks resident (grid = CUs x resident blocks, fewer when
-// the buffer is small), chunks of at most max_chunk_iters block iterations claimed dynamically, at
-// least about 16 chunks per block when the buffer is small so that the claiming can still balance
-// the load.
+// the buffer is small), chunks of at most max_chunk_iters block iterations claimed dynamically.
 struct Grid {
     uint32_t blocks;
     Work work;
@@ -96,8 +94,11 @@ inline Grid plan_grid(uint64_t N, int num_cus, int blocks_per_cu, unsigned long 
     const uint64_t resident = (uint64_t)num_cus * (uint64_t)blocks_per_cu;
     uint64_t iters = (N + kIter - 1) / kIter;
     if (iters < 1) iters = 1;
+    // about 16 chunks per block when the buffer is small, but never so short that the counter
+    // becomes the bottleneck (a quarter of a million claims take 5 ms, whatever the kernel does)
+    const uint64_t min_chunk_iters = max_chunk_iters < 8 ? max_chunk_iters : 8;
     uint64_t chunk_iters = iters / (resident * 16);
-    if (chunk_iters < 1) chunk_iters = 1;
+    if (chunk_iters < min_chunk_iters) chunk_iters = min_chunk_iters;
     if (chunk_iters > max_chunk_iters) chunk_iters = max_chunk_iters;
     g.work.counter = counter;
     g.work.chunk = chunk_iters * kIter;
