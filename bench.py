@@ -395,15 +395,15 @@ def study_quantiser(args, np, torch, B, synth, dev):
 
 
 def measure_copy_kernel(torch, src_buf, alloc):
-    """Bandwidth of a plain elementwise copy (read 4 B, write 4 B per element) of 2^30 fp32, measured
+    """Bandwidth of a plain elementwise copy (read 4 B, write 4 B per element) of up to 2^30 fp32, measured
     in this process: the nominal 8 TB/s is never reached by any kernel, so the step is also
     reported as a fraction of this."""
-    n = 1 << 30
+    n = min(1 << 30, src_buf.numel())
     src = src_buf[:n]
     dst = alloc(n, torch.float32)
     best = 0.0
-    for name, fn in (("elementwise x*2 over 2^30 fp32", lambda: torch.mul(src, 2.0, out=dst)),
-                     ("tensor copy 2^30 fp32", lambda: dst.copy_(src))):
+    for name, fn in ((f"elementwise x*2 over {n} fp32", lambda: torch.mul(src, 2.0, out=dst)),
+                     (f"tensor copy of {n} fp32", lambda: dst.copy_(src))):
         fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()

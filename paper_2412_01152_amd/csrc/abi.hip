@@ -2,6 +2,10 @@
 // and the launch sequence of each call.  Everything is enqueued on the caller's stream; nothing
 // here allocates, frees or waits for the device.
 #include <math.h>
+
+#include <algorithm>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "finalize_kernels.h"
@@ -52,6 +56,22 @@ int32_t check_segments(const uint64_t* seg, uint32_t T, uint64_t N) {
     return DILOCO_OK;
 }
 
+// Write window of pass B in ticks of the device's constant-rate clock; period 0 (write at once)
+// when the clock rate cannot be read or DILOCO_WRITE_PHASE=0 is set in the environment.
+WritePhase write_phase_ticks() {
+    WritePhase w = {0, 0};
+    const char* env = getenv("DILOCO_WRITE_PHASE");
+    if (env && env[0] == '0') return w;
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return w;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz < 1000) return w;
+    int period_us = kWritePeriodUs, window_us = kWriteWindowUs;
+    if (env) sscanf(env, "%d,%d", &period_us, &window_us);
+    w.period = (uint32_t)((long long)khz * period_us / 1000);
+    w.window = (uint32_t)((long long)khz * window_us / 1000);
+    return w;
+}
+
 int32_t num_compute_units(int* out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -83,6 +103,7 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     p.stream = stream;
     int32_t rc = num_compute_units(&p.num_cus);
     if (rc) return rc;
+    p.write_phase = write_phase_ticks();
     hipError_t e = upload_offsets(seg_host, T + 1, (uint64_t*)(ws + L.seg), stream);
     if (e != hipSuccess) return (int32_t)e;
     const size_t words = (L.total - L.stats) / sizeof(uint64_t);
@@ -124,7 +145,7 @@ hipError_t run_stats(const Src& src, const Pass& p, uint32_t phase) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr auto kernel = stats_kernel<Src, false>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0, phase, kChunkItersRead);
+    Grid g = plan_grid(p.N, p.num_cus, kBlocksPerCuStreamRead, p.counters + 0, phase, kChunkItersRead);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
                        g.work, p.stats, p.pivot, (float*)nullptr);
@@ -135,12 +156,12 @@ hipError_t run_stats(const Src& src, const Pass& p, uint32_t phase) {
 
 template <class Src>
 hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
-    constexpr auto kernel = quant_kernel<Src, kBinCopiesStream>;
+    constexpr auto kernel = quant_kernel<Src, kBinCopiesStream, kStageIters>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
                        kChunkItersWrite);
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
-                       g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
+                       g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt}, p.write_phase);
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
@@ -185,7 +206,7 @@ hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t
     hipError_t e;
     if (delta) {
         constexpr auto kernel = outer_fp32_kernel<kOut>;
-        const int bpc = resident_blocks_per_cu<kernel>();
+        const int bpc = std::min(resident_blocks_per_cu<kernel>(), kBlocksPerCuOuter);
         Grid g = counter ? plan_grid(N, num_cus, bpc, counter, phase, kChunkItersOuter)
                          : plan_static(N, num_cus, bpc, phase);
         (void)mark(0, stream);
@@ -194,7 +215,7 @@ hipError_t run_outer(float* theta, float* mom, const float* delta, const uint8_t
         e = hipGetLastError();
     } else {
         constexpr auto kernel = outer_coded_kernel<kOut>;
-        const int bpc = resident_blocks_per_cu<kernel>();
+        const int bpc = std::min(resident_blocks_per_cu<kernel>(), kBlocksPerCuOuter);
         Grid g = counter ? plan_grid(N, num_cus, bpc, counter, phase, kChunkItersOuter)
                          : plan_static(N, num_cus, bpc, phase);
         (void)mark(0, stream);

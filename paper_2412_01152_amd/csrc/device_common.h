@@ -17,6 +17,15 @@ constexpr int kUnroll = 4;                          // loads in flight per strea
 // measurably faster with sixteen.
 constexpr int kBinCopiesStream = 1;
 constexpr int kBinCopiesReduce = 16;
+// Iterations of codes (4 KiB each) a block of pass B can hold back in LDS, and the write window of
+// the staged codes in microseconds: the first kWriteWindowUs of every kWritePeriodUs.
+constexpr int kStageIters = 8;
+constexpr int kWritePeriodUs = 40;
+constexpr int kWriteWindowUs = 10;
+struct WritePhase {
+    uint32_t period;   // in ticks of wall_clock64(); 0 = write every iteration's codes at once
+    uint32_t window;   // the first `window` ticks of each period are the write window
+};
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
 constexpr uint32_t kNoSegment = 0xffffffffu;
@@ -39,6 +48,8 @@ static_assert((long long)(kFlushIters + 2) * kIter * (1ll << 23) <= (1ll << kCou
 typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));
 typedef uint16_t u16x4_u __attribute__((ext_vector_type(4), aligned(2)));
 typedef uint32_t u32_u __attribute__((aligned(1)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_u __attribute__((ext_vector_type(4), aligned(1)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Every array here is streamed once per pass, so loads and stores carry the non-temporal hint
@@ -70,6 +81,14 @@ __device__ __forceinline__ void st_u8x4(uint8_t* p, uint32_t v) {
     __builtin_nontemporal_store(v, (u32_u*)p);
 #else
     *(u32_u*)p = v;
+#endif
+}
+
+__device__ __forceinline__ void st_u8x16(uint8_t* p, u32x4 v) {
+#if DILOCO_NT
+    __builtin_nontemporal_store((u32x4_u)v, (u32x4_u*)p);
+#else
+    *(u32x4_u*)p = (u32x4_u)v;
 #endif
 }
 

@@ -21,6 +21,7 @@ struct Pass {
     unsigned long long* ocnt;   // device, [T][2]
     unsigned long long* counters;   // device, [kNumCounters], zero at the start of the call
     int num_cus;
+    WritePhase write_phase;     // when pass B writes its staged codes
     hipStream_t stream;
 };
 
@@ -78,6 +79,12 @@ constexpr uint64_t kChunkItersWrite = 8;
 constexpr uint64_t kChunkItersStoreAcc = 4;
 constexpr uint64_t kChunkItersOuter = 4;      // coded form: 28.24 ms static, 28.00 at 8, 27.92 at 4, 27.73 at 2
 inline uint64_t chunk_iters_reduce_write(uint32_t W) { return W <= 4 ? 64 : 16; }
+// Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory
+// system): the pass that only reads two fp32 streams (11.62 ms with the 7 that fit, 11.36 with 2,
+// 11.27 with 1) and the outer step (26.96 ms with the 6 that fit, 26.64 with 2, 27.18 with 1).  The
+// other kernels are fastest with all the blocks their LDS use admits (3 or 4).
+constexpr int kBlocksPerCuStreamRead = 1;
+constexpr int kBlocksPerCuOuter = 2;
 inline uint32_t host_phase(const void* p, int elem_bytes) {
     return (uint32_t)((uintptr_t)p / (uintptr_t)elem_bytes) & (kAlignElems - 1);
 }

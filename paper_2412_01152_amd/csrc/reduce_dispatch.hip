@@ -48,12 +48,12 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
 template <int W, bool kLocal, bool kTrueDiv>
 hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
-    constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce>;
+    constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce, 0>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
                        chunk_iters_reduce_write(W));
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
-                       p.T, p.N, g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt});
+                       p.T, p.N, g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt}, p.write_phase);
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
