@@ -24,6 +24,7 @@ struct SrcPseudoGrad {
     const float* theta_outer;
     const void* theta_local;
     static constexpr int kLdsFloats = 0;
+    static constexpr int kStage = kStageIters;      // pass B holds its codes back for the write window
     struct Raw {
         f32x4 a, b;
     };
@@ -56,6 +57,7 @@ struct SrcPseudoGrad {
 struct SrcF32 {
     const float* x;
     static constexpr int kLdsFloats = 0;
+    static constexpr int kStage = 0;                // measured: 8.58 ms writing at once, 8.77 ms staged
     struct Raw {
         f32x4 a;
     };
@@ -86,6 +88,7 @@ struct SrcReduce {
     float div;                 // the divisor (kTrueDiv) or its exact reciprocal
     float* lds;                // W tables of 256 floats
     static constexpr int kLdsFloats = W * kBuckets;
+    static constexpr int kStage = 0;                // the LDS goes to the bin copies and the tables
     struct Raw {
         uint32_t c[kW];
         f32x4 l;
@@ -340,7 +343,8 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
 // is full: HBM then sees long read phases and short write phases.  Nobody waits for anybody: a
 // block looks at the clock after each iteration and carries on.  Measured in a standalone kernel
 // with the same access pattern: 6.24 -> 6.66 TB/s with the codes far from the inputs, 5.46 -> 6.3-6.5
-// TB/s with everything side by side.
+// TB/s with everything side by side.  In this kernel: 14.35 -> 14.09 ms for stage 1's pass B at the
+// 10B size.  Sources whose pass B needs its LDS for other things, or gains nothing, set kStage = 0.
 template <class Src, int kCopies, int kStage>
 __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, Work work,

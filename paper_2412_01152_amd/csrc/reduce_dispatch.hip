@@ -48,7 +48,7 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
 template <int W, bool kLocal, bool kTrueDiv>
 hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
-    constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce, 0>;
+    constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce, Src::kStage>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
                        chunk_iters_reduce_write(W));
     (void)mark(2, p.stream);
