@@ -36,8 +36,9 @@
  *     pass of diloco_pseudograd_quantize holds its output codes back in on-chip memory and writes
  *     them during a periodic window of the device's constant-rate clock (the first 10 us of every
  *     40 us), which the memory system serves faster than a steady trickle of writes among the
- *     reads.  DILOCO_WRITE_PHASE=0 makes it write every iteration's codes at once;
- *     DILOCO_WRITE_PHASE=<period_us>,<window_us> changes the timing.  Results do not depend on it.
+ *     reads; buffers below 2^27 elements are written at once.  DILOCO_WRITE_PHASE=0 writes at once
+ *     at every size; DILOCO_WRITE_PHASE=<period_us>,<window_us> sets the timing and applies at
+ *     every size.  Results do not depend on it.
  */
 #ifndef DILOCO_MI355_H
 #define DILOCO_MI355_H

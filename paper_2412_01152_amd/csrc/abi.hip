@@ -103,7 +103,9 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     p.stream = stream;
     int32_t rc = num_compute_units(&p.num_cus);
     if (rc) return rc;
-    p.write_phase = write_phase_ticks();
+    // a launch shorter than a few periods only loses by waiting for its window (an explicit
+    // DILOCO_WRITE_PHASE=<period>,<window> applies at any size)
+    p.write_phase = (N >= kMinPhasedElems || getenv("DILOCO_WRITE_PHASE")) ? write_phase_ticks() : WritePhase{0, 0};
     hipError_t e = upload_offsets(seg_host, T + 1, (uint64_t*)(ws + L.seg), stream);
     if (e != hipSuccess) return (int32_t)e;
     const size_t words = (L.total - L.stats) / sizeof(uint64_t);

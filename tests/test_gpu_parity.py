@@ -395,3 +395,32 @@ def test_few_distinct_values_reconstruct(B, oracle_mod):
     dec = t2n(luts)[0][t2n(codes)]
     assert np.abs(dec.astype(np.float64) - t2n(d)).max() <= 2.0 ** -21 * w
     check_luts(t2n(luts), o_luts, o_codes, [0, n], o_qp)
+
+
+# ---------------------------------------------------------------------------------------------
+# stage 1 with the codes held back for the write window (the path large buffers take), forced at
+# small sizes through the library's environment switch: ragged segments, heads and tails, a
+# misaligned view, bf16, and windows so short or so long that either every flush is forced by a full
+# staging area or nearly every iteration falls inside a window
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("timing", ["40,10", "100000,1", "10,9"])
+@pytest.mark.parametrize("local_dtype", [torch.float32, torch.bfloat16])
+def test_stage1_staged_code_writes(B, oracle_mod, monkeypatch, timing, local_dtype):
+    monkeypatch.setenv("DILOCO_WRITE_PHASE", timing)
+    sizes = synth.ragged_sizes(1_500_000) + [4096 * 9 + 5, 130, 4096 * 33]
+    theta, locals_, off = synth.make_inputs(sizes, 1, device=DEV, local_dtype=local_dtype)
+    _check_stage1(B, oracle_mod, theta, locals_[0], off, f"staged writes, timing {timing}")
+    # a view that starts 3 elements into its buffer, output codes 5 bytes into theirs
+    n = theta.numel()
+    th_buf = torch.zeros(n + 8, dtype=torch.float32, device=DEV)
+    lo_buf = torch.zeros(n + 8, dtype=local_dtype, device=DEV)
+    co_buf = torch.zeros(n + 16, dtype=torch.uint8, device=DEV)
+    th_buf[3:3 + n] = theta
+    lo_buf[3:3 + n] = locals_[0]
+    codes, luts, qp = B.pseudograd_quantize(th_buf[3:3 + n], lo_buf[3:3 + n], off, codes_out=co_buf[5:5 + n])
+    monkeypatch.setenv("DILOCO_WRITE_PHASE", "0")
+    ref = B.pseudograd_quantize(theta, locals_[0], off)
+    torch.cuda.synchronize()
+    assert torch.equal(codes, ref[0]) and torch.allclose(luts, ref[1], rtol=1e-6, atol=0)
+    assert int(co_buf[:5].sum()) == 0 and int(co_buf[5 + n:].sum()) == 0          # nothing written outside
