@@ -5,8 +5,8 @@ memory, at a scale of tens of GiB (the outer step alone: 27.0 to 29.9 ms over pl
 only by a shift).  With one allocation per buffer the placement differs from process to process;
 buffers carved from a single allocation made first thing in a process land in the same place every
 time, and the same layout then reproduces to 0.1 %.  The arena is that single allocation, and
-`place_outer_state` picks, by timing the outer step on a few candidate shifts before any data is
-written, the shift at which theta_outer / theta_local / momentum are carved.
+`place_outer_state` picks, by timing the two placement-sensitive kernels on a few candidate shifts
+before any data is written, the shift at which theta_outer / theta_local / momentum are carved.
 
 This is memory plumbing around the library: nothing here touches the values.
 """
@@ -50,37 +50,48 @@ class Arena:
 
 def place_outer_state(arena: Arena, N: int, seg_offsets: Sequence[int], shifts_gib: Sequence[int],
                       tail_bytes: int, log=None) -> int:
-    """Times outer_nesterov_step (coded form) with theta at shift s, theta_local at s + 4N and
-    momentum at s + 8N bytes of the arena, the byte arrays behind them, for every candidate shift, and
-    returns the fastest shift in bytes.  The memory is used as it is (timing does not depend on the
-    values); the caller fills its buffers afterwards.  tail_bytes = what must still fit behind the
-    three fp32 arrays."""
+    """Times, for every candidate shift s, the two kernels whose speed depends on where the state lies
+    and not on its values - the statistics pass of diloco_pseudograd_quantize (reads theta_outer and
+    theta_local) and outer_nesterov_step (updates theta_outer and momentum in place) - with theta at
+    s, theta_local at s + 4N and momentum at s + 8N bytes of the arena and the byte arrays behind
+    them, and returns the shift with the smallest sum, in bytes.  The memory is used as it is; the
+    caller fills its buffers afterwards.  tail_bytes = what must still fit behind the three fp32
+    arrays."""
     dev = arena.buf.device
     T = len(seg_offsets) - 1
     lut = torch.zeros((T, 256), dtype=torch.float32, device=dev)
+    lut_out = torch.empty((T, 256), dtype=torch.float32, device=dev)
+    qp = B.new_qparams(T, dev)
     ws = B.new_workspace(T, dev)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for e in events:
+        e.record()
     best: Tuple[float, int] = (float("inf"), 0)
     for s_gib in shifts_gib:
         shift = s_gib * GiB
         if shift + 12 * N + tail_bytes + 8 * ALIGN > arena.nbytes:
             continue
         theta = arena.carve(N, torch.float32, at=shift)
-        arena.carve(N, torch.float32)                       # theta_local's place
+        local = arena.carve(N, torch.float32)
         mom = arena.carve(N, torch.float32)
-        arena.carve(tail_bytes - N, torch.uint8)            # the other byte arrays' place
-        codes = arena.carve(N, torch.uint8)                 # the reduced codes come last
-        times = []
-        for _ in range(3):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            B.outer_step(theta, mom, 0.0, 0.0, delta_codes=codes, delta_lut=lut, seg_offsets=seg_offsets,
-                         workspace=ws)
-            e1.record()
+        arena.carve(tail_bytes - 2 * N, torch.uint8)        # the peers' codes
+        codes1 = arena.carve(N, torch.uint8)                # stage 1 writes here
+        codes2 = arena.carve(N, torch.uint8)                # the outer step reads these
+        t_stats, t_outer = [], []
+        for _ in range(2):
+            B.profile_passes([e.cuda_event for e in events])
+            B.pseudograd_quantize(theta, local, seg_offsets, codes_out=codes1, lut_out=lut_out, qparams_out=qp,
+                                  workspace=ws)
             torch.cuda.synchronize(dev)
-            times.append(e0.elapsed_time(e1))
-        ms = min(times[1:])
+            t_stats.append(events[0].elapsed_time(events[1]))
+            B.outer_step(theta, mom, 0.0, 0.0, delta_codes=codes2, delta_lut=lut, seg_offsets=seg_offsets,
+                         workspace=ws)
+            torch.cuda.synchronize(dev)
+            t_outer.append(events[0].elapsed_time(events[1]))
+        B.profile_passes(None)
+        ms = min(t_stats) + min(t_outer)
         if log:
-            log(f"[arena] outer step with the state at +{s_gib} GiB: {ms:.2f} ms")
+            log(f"[arena] state at +{s_gib} GiB: statistics pass {min(t_stats):.2f} ms + outer step {min(t_outer):.2f} ms")
         if ms < best[0]:
             best = (ms, shift)
     arena.pos = 0

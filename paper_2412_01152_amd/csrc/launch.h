@@ -77,7 +77,7 @@ struct Grid {
 constexpr uint64_t kChunkItersRead = 128;
 constexpr uint64_t kChunkItersWrite = 8;
 constexpr uint64_t kChunkItersStoreAcc = 4;
-constexpr uint64_t kChunkItersOuter = 4;      // coded form: 28.24 ms static, 28.00 at 8, 27.92 at 4, 27.73 at 2
+constexpr uint64_t kChunkItersOuter = 2;      // coded form, 2 blocks per CU: 26.84 ms at 8, 26.62 at 4, 26.04 at 2, 33.0 at 1
 inline uint64_t chunk_iters_reduce_write(uint32_t W) { return W <= 4 ? 64 : 16; }
 // Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory
 // system): the pass that only reads two fp32 streams (11.62 ms with the 7 that fit, 11.36 with 2,
