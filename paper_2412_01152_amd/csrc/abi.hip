@@ -159,8 +159,8 @@ hipError_t run_stats(const Src& src, const Pass& p, uint32_t phase) {
 template <class Src>
 hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     constexpr auto kernel = quant_kernel<Src, kBinCopiesStream, Src::kStage>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
-                       kChunkItersWrite);
+    Grid g = plan_grid(p.N, p.num_cus, std::min(resident_blocks_per_cu<kernel>(), kBlocksPerCuStreamWrite),
+                       p.counters + 1, host_phase(codes, 1), kChunkItersWrite);
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, src, p.seg, p.T, p.N,
                        g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt}, p.write_phase);

@@ -82,8 +82,12 @@ inline uint64_t chunk_iters_reduce_write(uint32_t W) { return W <= 4 ? 64 : 16; 
 // Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory
 // system): the pass that only reads two fp32 streams (11.62 ms with the 7 that fit, 11.36 with 2,
 // 11.27 with 1) and the outer step (26.96 ms with the 6 that fit, 26.64 with 2, 27.18 with 1).  The
-// other kernels are fastest with all the blocks their LDS use admits (3 or 4).
+// Pass B of the streaming sources: 4 (what the staged codes leave room for anyway; the stored-array
+// source, which does not stage, 8.54 ms with the 6 that fit, 8.35 with 4).  The reduce-source
+// kernels are fastest with all the blocks their LDS use admits (3 or 4): their table look-ups need
+// the waves.
 constexpr int kBlocksPerCuStreamRead = 1;
+constexpr int kBlocksPerCuStreamWrite = 4;
 constexpr int kBlocksPerCuOuter = 2;
 inline uint32_t host_phase(const void* p, int elem_bytes) {
     return (uint32_t)((uintptr_t)p / (uintptr_t)elem_bytes) & (kAlignElems - 1);
