@@ -1,8 +1,8 @@
 """One device allocation for all large buffers, and a measured choice of where the outer state goes.
 
 Why.  On an MI355X the streaming kernels' speed depends on where their buffers lie in physical
-memory, at a scale of tens of GiB (the outer step alone: 27.0 to 29.9 ms over placements that differ
-only by a shift).  With one allocation per buffer the placement differs from process to process;
+memory, at a scale of tens of GiB (with 4 GiB arrays the outer step runs at 5.4 TB/s when momentum
+lies within 64 GiB of theta_outer and at 6.3 TB/s from 96 GiB on).  With one allocation per buffer the placement differs from process to process;
 buffers carved from a single allocation made first thing in a process land in the same place every
 time, and the same layout then reproduces to 0.1 %.  The arena is that single allocation, and
 `place_outer_state` picks, by timing the two placement-sensitive kernels on a few candidate shifts
