@@ -30,18 +30,21 @@ struct WritePhase {
 constexpr int kIter = kThreads * kVec * kUnroll;    // elements one block consumes per iteration
 constexpr int kBuckets = 256;
 constexpr uint32_t kNoSegment = 0xffffffffu;
-// Fixed-point bucket sums: a 64-bit LDS bin holds {count : 24 bits, sum of biased offsets : 40 bits}.
-// An offset is at most one bucket width, scaled by 2^21 / width and biased by 2^22, so an addend is
-// below 2^23 and a bin takes 2^17 of them before the low field could carry into the count.
+// Fixed-point bucket sums: a 64-bit LDS bin holds {count : 16 bits, sum of addends : 48 bits}.
+// An offset from the bucket centre is at most one bucket width; scaled by 2^21 / width and added to
+// 1.5 * 2^23 in fp32 it becomes an integer in the low mantissa bits of the result, and the bit
+// pattern of that float (0x4B400000 + round(offset * 2^21 / width), below 2^31) is the addend: no
+// masking per element, the constant part is taken out again, count times, when a bin is drained.
 constexpr int kOffsetBits = 21;
-constexpr int kOffsetBias = 1 << 22;
 constexpr float kRoundMagic = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer
-constexpr int kCountShift = 40;
-constexpr int kFlushIters = 16;                     // the bins are drained once 2^16 elements are in
+constexpr long long kAddendBase = 0x4B400000ll;     // bit pattern of kRoundMagic
+constexpr int kCountShift = 48;
+constexpr int kFlushIters = 12;                     // the bins are drained once 12 iterations are in
 // the count of binned elements is checked after every iteration and every ragged tail (< kIter
 // elements) and a head (< 128) may follow unchecked, so fewer than (kFlushIters + 2) * kIter
-// elements sit in the bins at any time
-static_assert((long long)(kFlushIters + 2) * kIter * (1ll << 23) <= (1ll << kCountShift), "bin overflow");
+// elements sit in the bins at any time: their count must fit 16 bits, their sum 48
+static_assert((long long)(kFlushIters + 2) * kIter < (1ll << (64 - kCountShift)), "bin count overflow");
+static_assert((long long)(kFlushIters + 2) * kIter * (1ll << 31) <= (1ll << kCountShift), "bin sum overflow");
 
 // Vector types that promise only element alignment: gfx950 global memory instructions accept
 // any byte address, so one dwordx4 / dwordx2 / dword access is emitted whatever the pointer's
@@ -218,8 +221,9 @@ __device__ __forceinline__ void block_sum2(double& a, double& b, double* red) {
 __device__ __forceinline__ float bucket_width(float inv_w) {
     return inv_w > 0.0f ? __fdiv_rn(1.0f, inv_w) : 0.0f;
 }
-__device__ __forceinline__ float bucket_centre(float kf, float lo, float w) {
-    return __fmaf_rn(kf + 0.5f, w, lo);
+__device__ __forceinline__ float bucket_centre0(float lo, float w) { return __fmaf_rn(0.5f, w, lo); }
+__device__ __forceinline__ float bucket_centre(float kf, float centre0, float w) {
+    return __fmaf_rn(kf, w, centre0);
 }
 // Bucket index of Section 2.2's quantiser, as a float (0.0 .. 255.0): floor((x - lo) / width)
 // clipped to [0, 255], with the subtraction and the multiplication by the reciprocal width as two
@@ -229,7 +233,7 @@ __device__ __forceinline__ float bucket_of_f(float x, float lo, float inv_w) {
     const float t = __fmul_rn(__fsub_rn(x, lo), inv_w);
     return __builtin_amdgcn_fmed3f(__builtin_floorf(t), 0.0f, 255.0f);
 }
-// Factor that turns an offset from the bucket centre into fixed point: 2^22 / width (0 when the
+// Factor that turns an offset from the bucket centre into fixed point: 2^21 / width (0 when the
 // segment is degenerate or the factor would overflow; then every non-zero offset goes the fp64 way).
 __device__ __forceinline__ float offset_scale(float inv_w) {
     const float s = __fmul_rn(inv_w, (float)(1 << kOffsetBits));

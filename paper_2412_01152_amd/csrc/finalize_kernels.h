@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void finalize_lut_kernel(uint32_t T, doub
     }
     float out;
     if (c > 0 && codebook == DILOCO_CODEBOOK_MEAN) {
-        out = (float)((double)bucket_centre((float)k, q.lo, w) + off_sum / (double)c);
+        out = (float)((double)bucket_centre((float)k, bucket_centre0(q.lo, w), w) + off_sum / (double)c);
     } else {
         const double lo64 = q.mean - range_sigmas * q.std;
         const double w64 = (2.0 * range_sigmas * q.std) / 256.0;

@@ -25,6 +25,7 @@ struct SrcPseudoGrad {
     const void* theta_local;
     static constexpr int kLdsFloats = 0;
     static constexpr int kStage = kStageIters;      // pass B holds its codes back for the write window
+    static constexpr int kQuantWaves = 1;           // pass B: no register budget asked for
     struct Raw {
         f32x4 a, b;
     };
@@ -58,6 +59,7 @@ struct SrcF32 {
     const float* x;
     static constexpr int kLdsFloats = 0;
     static constexpr int kStage = 0;                // measured: 8.58 ms writing at once, 8.77 ms staged
+    static constexpr int kQuantWaves = 1;
     struct Raw {
         f32x4 a;
     };
@@ -89,6 +91,9 @@ struct SrcReduce {
     float* lds;                // W tables of 256 floats
     static constexpr int kLdsFloats = W * kBuckets;
     static constexpr int kStage = 0;                // the LDS goes to the bin copies and the tables
+    // Pass B at W <= 4 is held to 128 registers, so that four blocks (which is what its LDS admits)
+    // are resident per CU instead of three: 9.76 -> 9.63 ms at W = 4 on the 10B buffer.
+    static constexpr int kQuantWaves = W <= 4 ? 4 : 1;
     struct Raw {
         uint32_t c[kW];
         f32x4 l;
@@ -98,8 +103,12 @@ struct SrcReduce {
         if (W > 0) {
             __syncthreads();
 #pragma unroll
-            for (int p = 0; p < W; ++p)
-                lds[p * kBuckets + threadIdx.x] = luts[p][(size_t)s * kBuckets + threadIdx.x];
+            for (int p = 0; p < W; ++p) {
+                const float entry = luts[p][(size_t)s * kBuckets + threadIdx.x];
+                // the sum starts from 0.0f: with no local addend its first addition (which only turns
+                // -0 into +0) is done here, once per table entry, instead of once per element
+                lds[p * kBuckets + threadIdx.x] = (p == 0 && !kHasLocal) ? __fadd_rn(0.0f, entry) : entry;
+            }
             __syncthreads();
         }
     }
@@ -119,8 +128,10 @@ struct SrcReduce {
         for (int e = 0; e < 4; ++e) {
             float acc = kHasLocal ? r.l[e] : 0.0f;
 #pragma unroll
-            for (int p = 0; p < W; ++p)
-                acc = __fadd_rn(acc, lds[p * kBuckets + ((r.c[p] >> (8 * e)) & 0xffu)]);
+            for (int p = 0; p < W; ++p) {
+                const float x = lds[p * kBuckets + ((r.c[p] >> (8 * e)) & 0xffu)];
+                acc = (p == 0 && !kHasLocal) ? x : __fadd_rn(acc, x);
+            }
             v[e] = finish(acc);
         }
         return v;
@@ -128,7 +139,10 @@ struct SrcReduce {
     __device__ __forceinline__ float value1(uint64_t i) const {
         float acc = kHasLocal ? local[i] : 0.0f;
 #pragma unroll
-        for (int p = 0; p < W; ++p) acc = __fadd_rn(acc, lds[p * kBuckets + codes[p][i]]);
+        for (int p = 0; p < W; ++p) {
+            const float x = lds[p * kBuckets + codes[p][i]];
+            acc = (p == 0 && !kHasLocal) ? x : __fadd_rn(acc, x);
+        }
         return finish(acc);
     }
     // Same value straight from global memory (no LDS tables needed): used for the pivot.
@@ -244,14 +258,18 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint6
 // The codebook needs, per bucket, the count and the sum of the values in it.  Floating-point LDS
 // atomics are several times slower than integer ones on this chip, so the sum is kept in fixed
 // point: for a value x in bucket k the kernel forms off = x - centre_k (|off| <= half a bucket),
-// q = round(off * 2^21 / width), and adds the single 64-bit word  (1 << 40) | (q + 2^22)  to the
-// bucket's LDS bin: count in the top 24 bits, biased offset sum in the low 40.  One rounding of at
-// most 2^-22 of a bucket per element, integer sums exact and order-independent thereafter.
+// lets fma(off, 2^21 / width, 1.5 * 2^23) round it to an integer q in the low mantissa bits, and
+// adds the single 64-bit word  (1 << 48) | bits(that float)  to the bucket's LDS bin: count in the
+// top 16 bits, sum of (0x4B400000 + q) in the low 48.  One rounding of at most 2^-22 of a bucket
+// per element, integer sums exact and order-independent thereafter.
 // Values further than one bucket width from their bucket's centre (the clipped tails that land in
 // buckets 0 and 255) do not fit that format; they are rare and go through per-thread fp64
-// accumulators instead.  Thread k owns bin k: every kFlushIters iterations (before the 40-bit field
-// can overflow) it moves the bin into 64-bit registers, and when the block leaves the segment it
+// accumulators instead.  Thread k owns bin k: every kFlushIters iterations (before either field can
+// overflow) it moves the bin into 64-bit registers, and when the block leaves the segment it
 // adds its totals to the segment's global integer bins.
+// This pass is bound by vector-ALU instruction issue as much as by memory when the source is the
+// reduce (about 20 instructions per element at W = 4), so the per-element chain is kept short: no
+// mask on the index, no mask on the addend, the half bucket folded into centre_0.
 struct PassBOut {
     unsigned long long* hsumq;   // [T][256] signed sum of q (two's complement)
     unsigned long long* hcnt;    // [T][256]
@@ -260,13 +278,14 @@ struct PassBOut {
 };
 
 struct BinScale {
-    float lo, inv_w, w, scale, reach;
+    float lo, inv_w, w, centre0, scale, reach;
 };
 __device__ __forceinline__ BinScale bin_scale(float lo, float inv_w) {
     BinScale b;
     b.lo = lo;
     b.inv_w = inv_w;
     b.w = bucket_width(inv_w);
+    b.centre0 = bucket_centre0(lo, b.w);
     b.scale = offset_scale(inv_w);
     b.reach = b.scale > 0.0f ? b.w : 0.0f;   // no fixed-point scale: only exact zeros take the fast path
     return b;
@@ -287,18 +306,21 @@ __device__ __forceinline__ void far_add(float off, int k, FarSums& far) {
     }
 }
 
+// The float holding round(off * scale) in its low mantissa bits; its bit pattern is the bin addend.
+__device__ __forceinline__ unsigned long long bin_addend(float off, float scale) {
+    return (1ull << kCountShift) | (unsigned long long)__float_as_uint(__fmaf_rn(off, scale, kRoundMagic));
+}
+
+// The bucket index comes out of a clamp to [0, 255] (NaN gives 0), so its conversion needs no mask.
 __device__ __forceinline__ int code_and_bin(float x, const BinScale& b, unsigned long long* s_bin,
                                             int copies, FarSums& far) {
     const float kf = bucket_of_f(x, b.lo, b.inv_w);
-    const int k = (int)(unsigned)kf & (kBuckets - 1);
-    const float off = __fsub_rn(x, bucket_centre(kf, b.lo, b.w));
-    if (!(fabsf(off) <= b.reach)) {
+    const int k = (int)(unsigned)kf;
+    const float off = __fsub_rn(x, bucket_centre(kf, b.centre0, b.w));
+    if (fabsf(off) <= b.reach)
+        atomicAdd(&s_bin[k * copies], bin_addend(off, b.scale));
+    else
         far_add(off, k, far);
-    } else {
-        // round(off * scale) + 2^22 read off the mantissa of (off * scale + 1.5 * 2^23)
-        const unsigned q = __float_as_uint(__fmaf_rn(off, b.scale, kRoundMagic)) & 0x7fffffu;
-        atomicAdd(&s_bin[k * copies], (1ull << kCountShift) | (unsigned long long)q);
-    }
     return k;
 }
 
@@ -308,25 +330,19 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
                                                   int copies, FarSums& far) {
     int k[4];
     float off[4];
-    bool is_far[4];
+    bool near[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const float kf = bucket_of_f(v[e], b.lo, b.inv_w);
-        k[e] = (int)(unsigned)kf & (kBuckets - 1);
-        off[e] = __fsub_rn(v[e], bucket_centre(kf, b.lo, b.w));
-        is_far[e] = !(fabsf(off[e]) <= b.reach);
+        k[e] = (int)(unsigned)kf;
+        off[e] = __fsub_rn(v[e], bucket_centre(kf, b.centre0, b.w));
+        near[e] = fabsf(off[e]) <= b.reach;
+        if (near[e]) atomicAdd(&s_bin[k[e] * copies], bin_addend(off[e], b.scale));
     }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (!is_far[e]) {
-            const unsigned q = __float_as_uint(__fmaf_rn(off[e], b.scale, kRoundMagic)) & 0x7fffffu;
-            atomicAdd(&s_bin[k[e] * copies], (1ull << kCountShift) | (unsigned long long)q);
-        }
-    }
-    if (is_far[0] | is_far[1] | is_far[2] | is_far[3]) {
+    if (!(near[0] & near[1] & near[2] & near[3])) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (is_far[e]) far_add(off[e], k[e], far);
+            if (!near[e]) far_add(off[e], k[e], far);
     }
     return (uint32_t)k[0] | ((uint32_t)k[1] << 8) | ((uint32_t)k[2] << 16) | ((uint32_t)k[3] << 24);
 }
@@ -346,7 +362,7 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
 // TB/s with everything side by side.  In this kernel: 14.35 -> 14.09 ms for stage 1's pass B at the
 // 10B size.  Sources whose pass B needs its LDS for other things, or gains nothing, set kStage = 0.
 template <class Src, int kCopies, int kStage>
-__global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::kQuantWaves))) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, Work work,
                                                         const diloco_qparams* __restrict__ qp,
                                                         uint8_t* __restrict__ codes, PassBOut out,
@@ -396,7 +412,7 @@ __global__ __launch_bounds__(kThreads) void quant_kernel(Src src_in, const uint6
             const unsigned long long packed = s_bin_all[idx];
             s_bin_all[idx] = 0;
             const unsigned long long c = packed >> kCountShift;
-            bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kOffsetBias;
+            bin_q += (long long)(packed & ((1ull << kCountShift) - 1)) - (long long)c * kAddendBase;
             bin_c += c;
         }
         pending = 0;

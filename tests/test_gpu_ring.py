@@ -92,8 +92,14 @@ def test_ring_chain_and_one_shot_error(B, oracle_mod, kind):
     same = t2n(r_codes) == c
     assert same.mean() > 1 - 1e-3, f"{(~same).sum()} of {n} final codes differ from the oracle's trip"
     assert np.abs(t2n(r_codes).astype(np.int32) - c.astype(np.int32)).max() <= 1
+    # codebook entries: the per-call bar, plus what the flipped elements can do to a bucket's average
+    # (each one moves a value lying at a bucket edge between two neighbouring buckets: at most one
+    # bucket width over the bucket's count)
     w_ring = 12 * float(q["std"][0]) / 256
-    assert np.all(np.abs(r_val[same] - l[0][c[same]]) <= 1e-6 * np.maximum(np.abs(l[0][c[same]]), w_ring))
+    flips = int((~same).sum())
+    count = np.bincount(c, minlength=256).astype(np.float64)
+    tol = 1e-6 * np.maximum(np.abs(l[0]), w_ring) + flips * w_ring / np.maximum(count - flips, 1.0)
+    assert np.all(np.abs(r_val[same] - l[0][c[same]]) <= tol[c[same]])
 
     exact = np.mean(np.stack([x.astype(np.float64) for x in d]), axis=0)
     sd = exact.std()
