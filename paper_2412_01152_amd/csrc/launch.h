@@ -72,13 +72,13 @@ struct Grid {
 // 12.12 ms at 32, 11.73 ms at 128), passes that also write with short ones, which keep the blocks'
 // working set within a narrower window of addresses (stage 1 pass B: 15.32 ms at 32, 14.94 ms at 8;
 // bf16: 12.99 -> 12.42 ms; pass A of the reduce when it stores the accumulation, W = 14: 33.4 ms at
-// 32, 32.0 ms at 4).  Pass B of the reduce source recomputing from W code streams is the exception
-// at small W (W = 4: 9.66 ms at 64, 9.93 ms at 8; W = 8: 16.6 against 16.1 ms).
+// 32, 32.0 ms at 4).  Pass B of the reduce source, which recomputes the values from W code streams, sits
+// in between (W = 4, four resident blocks: 9.56 ms at 8, 9.36 at 16, 9.48 at 32, 9.60 at 64).
 constexpr uint64_t kChunkItersRead = 128;
 constexpr uint64_t kChunkItersWrite = 8;
 constexpr uint64_t kChunkItersStoreAcc = 4;
 constexpr uint64_t kChunkItersOuter = 2;      // coded form, 2 blocks per CU: 26.84 ms at 8, 26.62 at 4, 26.04 at 2, 33.0 at 1
-inline uint64_t chunk_iters_reduce_write(uint32_t W) { return W <= 4 ? 64 : 16; }
+constexpr uint64_t kChunkItersReduceWrite = 16;
 // Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory
 // system): the pass that only reads two fp32 streams (11.62 ms with the 7 that fit, 11.36 with 2,
 // 11.27 with 1) and the outer step (26.96 ms with the 6 that fit, 26.64 with 2, 27.18 with 1).  The

@@ -50,7 +50,7 @@ hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* q
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
     constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce, Src::kStage>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
-                       chunk_iters_reduce_write(W));
+                       kChunkItersReduceWrite);
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt}, p.write_phase);
