@@ -65,6 +65,8 @@ def main():
                     help="quantiser: error of the 8-bit code for other clipping widths, the midpoint codebook and "
                          "per-row groups, on one decoder layer; ring: error and time of the per-hop ring reduce (requantised at every hop) against the "
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
+    ap.add_argument("--graph", action="store_true",
+                    help="configs 0-2: also record the step into a HIP graph and time its replays")
     ap.add_argument("--no-arena", action="store_true",
                     help="allocate every buffer separately instead of carving them from one arena whose "
                          "placement is chosen by timing the outer step (configs 2, 3 and 4)")
@@ -253,6 +255,23 @@ def main():
                      "GB/s": round(STAGE_BYTES[s] * N / (avg * 1e-3) / 1e9, 1),
                      "frac_of_peak": round(STAGE_BYTES[s] * N / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         log(f"[bench] {s}: {avg:.3f} ms  {stages[s]['GB/s']:.1f} GB/s ({100 * stages[s]['GB/s'] / HBM_PEAK_GBS:.1f}%)")
+    graph = None
+    if args.graph:
+        # the same step recorded once from the stream and replayed: no per-launch host work between kernels
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        graph = {"ms_per_step": round(g_ms, 3), "GB/s": round(step_bytes / (g_ms * 1e-3) / 1e9, 1)}
+        log(f"[bench] step replayed from a HIP graph: {g_ms:.3f} ms per step ({graph['GB/s']:.1f} GB/s); "
+            f"eager launches: {ms_per_step:.3f} ms")
     copy_ref = measure_copy_kernel(torch, local, alloc)
     log(f"[bench] plain copy kernel ({copy_ref['what']}): {copy_ref['GB/s']:.1f} GB/s; "
         f"step runs at {100 * value / copy_ref['GB/s']:.1f}% of it")
@@ -276,7 +295,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": KERNEL_BYTES[dominant] * N},
-        "kernels": kernels, "stages": stages, "extras": extras,
+        "kernels": kernels, "stages": stages, "extras": extras, "graph": graph,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(result), flush=True)

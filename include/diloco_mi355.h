@@ -19,7 +19,10 @@
  *     keeps no state between calls, and never synchronises the device.
  *   - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL = the null
  *     stream) and returns.  Host arrays (seg_offsets, pointer tables) are consumed before the call
- *     returns and may be reused at once.
+ *     returns and may be reused at once.  What is enqueued is kernels only - no copies, no memset
+ *     nodes, no events unless diloco_profile_passes asked for them - so the calls may be recorded
+ *     by a stream capture and replayed as a HIP graph (segment offsets and pointer tables are
+ *     frozen into the recording).
  *   - A flat buffer of N elements is cut into T contiguous "segments" (the paper's "tensors":
  *     the quantisation groups).  `seg_offsets` is a HOST array of T+1 ascending element offsets
  *     with seg_offsets[0] == 0 and seg_offsets[T] == N.  Empty segments are allowed.
