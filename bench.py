@@ -67,6 +67,10 @@ def main():
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
     ap.add_argument("--graph", action="store_true",
                     help="configs 0-2: also record the step into a HIP graph and time its replays")
+    ap.add_argument("--spread", action="store_true",
+                    help="configs 0-1: carve the buffers from the arena so that every kernel's written buffers lie "
+                         "about 100 GiB away from the buffers it reads (small buffers allocated side by side are "
+                         "the slow case on this memory system)")
     ap.add_argument("--no-arena", action="store_true",
                     help="allocate every buffer separately instead of carving them from one arena whose "
                          "placement is chosen by timing the outer step (configs 2, 3 and 4)")
@@ -134,6 +138,24 @@ def main():
             shift = 0
         log(f"[bench] arena of {arena.nbytes >> 30} GiB, state carved at +{shift >> 30} GiB")
 
+    # Small configurations, on request: three groups about 100 GiB apart - what stage 1, stage 2 and
+    # the outer step read (theta, theta_local, peer codes) | momentum and the stage-1 codes | the
+    # stage-2 codes - so that no kernel writes near what it reads.
+    spread = None
+    if cfg in (0, 1) and args.spread and not args.no_arena:
+        from paper_2412_01152_amd.arena import Arena
+        try:
+            arena = Arena(dev)
+            if arena.nbytes < (210 << 30):
+                raise RuntimeError(f"arena of {arena.nbytes >> 30} GiB is too small to spread over")
+            spread = {"read": 4 << 30, "state": 104 << 30, "out": 204 << 30}
+            shift = spread["read"]
+            log(f"[bench] arena of {arena.nbytes >> 30} GiB, buffers spread at +4 / +104 / +204 GiB")
+        except RuntimeError as e:
+            log(f"[bench] no arena ({e}); one allocation per buffer")
+            arena = None
+            torch.cuda.empty_cache()
+
     def alloc(numel, dtype, at=None):
         if arena is not None:
             try:
@@ -144,12 +166,18 @@ def main():
 
     theta = alloc(N, torch.float32, at=shift if arena is not None else None)
     local = alloc(N, torch.float32)
-    mom = alloc(N, torch.float32).zero_()
-    peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
+    if spread:
+        peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
+        mom = alloc(N, torch.float32, at=spread["state"]).zero_()
+        codes1 = alloc(N, torch.uint8)
+        codes2 = alloc(N, torch.uint8, at=spread["out"])
+    else:
+        mom = alloc(N, torch.float32).zero_()
+        peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
+        codes1 = alloc(N, torch.uint8)
+        codes2 = alloc(N, torch.uint8)
     peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=dev) for _ in range(W)]
-    codes1 = alloc(N, torch.uint8)
     lut1 = torch.empty((T, 256), dtype=torch.float32, device=dev)
-    codes2 = alloc(N, torch.uint8)
     lut2 = torch.empty((T, 256), dtype=torch.float32, device=dev)
     qp = B.new_qparams(T, dev)
     ws = B.new_workspace(T, dev)
