@@ -76,7 +76,13 @@ struct Grid {
 // in between (W = 4, four resident blocks: 9.56 ms at 8, 9.36 at 16, 9.48 at 32, 9.60 at 64).
 constexpr uint64_t kChunkItersRead = 128;
 constexpr uint64_t kChunkItersWrite = 8;
-constexpr uint64_t kChunkItersStoreAcc = 4;
+// Pass A of the reduce when it stores the accumulation: the more bytes an element moves, the longer
+// a chunk lasts and the shorter it may be before the counter binds (13 codes + fp32 addend in and
+// fp32 out, 21 B/element, ring-chunk calls: 45.7 ms at 4 iterations, 43.9 at 2; 4 codes in and fp32
+// out, 8 B/element: 22.9 ms at 4, 26.4 at 2).
+inline uint64_t chunk_iters_store_acc(uint32_t W, bool has_local) {
+    return W + (has_local ? 4u : 0u) + 4u >= 20u ? 2 : 4;
+}
 constexpr uint64_t kChunkItersOuter = 2;      // coded form, 2 blocks per CU: 26.84 ms at 8, 26.62 at 4, 26.04 at 2, 33.0 at 1
 constexpr uint64_t kChunkItersReduceWrite = 16;
 // Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory

@@ -36,7 +36,7 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     const uint32_t phase = acc_out ? host_phase(acc_out, 4)
                                    : (W > 0 ? host_phase(a.codes[0], 1) : host_phase(a.local, 4));
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0, phase,
-                       kWriteAcc ? kChunkItersStoreAcc : kChunkItersRead);
+                       kWriteAcc ? chunk_iters_store_acc(W, kLocal) : kChunkItersRead);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.work, p.stats, p.pivot, acc_out);
