@@ -781,6 +781,17 @@ def measured_traffic_bytes(kernel_name):
     return None
 
 
+def host_cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, layers, alloc):
     """Times the oracle's three stages on the first decoder layers of the same workload
     (9 tensors, 218,112,000 elements per layer), copied down from the device."""
@@ -808,7 +819,9 @@ def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, laye
         pcs.append(c)
         pls.append(l)
     del scratch
-    log(f"[bench] cpu baseline: sample of {n} elements, {threads} threads, setup {time.perf_counter() - t_setup:.1f}s")
+    cpu_model, logical = host_cpu_model(), os.cpu_count()
+    log(f"[bench] cpu baseline: sample of {n} elements, {threads} threads on {cpu_model} ({logical} logical CPUs), "
+        f"setup {time.perf_counter() - t_setup:.1f}s")
     t1 = time.perf_counter()
     c0, l0, _, _ = oracle.pseudograd_quantize(th, lo, sample_off)
     t2 = time.perf_counter()
@@ -841,7 +854,7 @@ def cpu_oracle_baseline(np, torch, synth, theta, local, off, sizes, cfg, W, laye
                       f"({n} elements in {len(sample_off) - 1} tensors, W={W}), same {bpe} B/element "
                       f"accounting; wall seconds per stage: {t2 - t1:.2f}/{t3 - t2:.2f}/{t5 - t4:.2f} "
                       f"(about {secs * threads:.0f} core-seconds)",
-            "seconds": round(secs, 3),
+            "seconds": round(secs, 3), "cpu": cpu_model, "logical_cpus": logical,
             "one_thread": {"value": round(gbs1, 3), "unit": "GB/s", "elements": n1, "seconds": round(secs1, 3)}}
 
 
