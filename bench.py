@@ -67,6 +67,9 @@ def main():
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
     ap.add_argument("--graph", action="store_true",
                     help="configs 0-2: also record the step into a HIP graph and time its replays")
+    ap.add_argument("--shard", type=int, default=1, metavar="K",
+                    help="config 2: one of K equal shards of every tensor (what one GPU of a K-GPU fully sharded "
+                         "node holds: the same 381 groups, a K-th of the elements), buffers spread as with --spread")
     ap.add_argument("--spread", action="store_true",
                     help="configs 0-1: carve the buffers from the arena so that every kernel's written buffers lie "
                          "about 100 GiB away from the buffers it reads (small buffers allocated side by side are "
@@ -106,6 +109,9 @@ def main():
     if cfg == 4:
         return (bench_config4_overlap if args.overlap else bench_config4)(args, np, torch, B, synth, dev)
     sizes = synth.config_segment_sizes(cfg)
+    sharded = cfg == 2 and args.shard > 1
+    if sharded:
+        sizes = [-(-s // args.shard) for s in sizes]
     off = synth.offsets_from_sizes(sizes)
     N, T = off[-1], len(sizes)
     W = 4 if cfg == 2 else synth.config_peers(cfg)
@@ -118,7 +124,7 @@ def main():
     # is then the same in every process (see paper_2412_01152_amd/arena.py), and the shift of the whole
     # group inside the arena is chosen by timing the outer step on a few candidates (setup, untimed).
     arena = None
-    if cfg == 2 and not args.no_arena:
+    if cfg == 2 and not sharded and not args.no_arena:
         from paper_2412_01152_amd.arena import Arena, place_outer_state
         need = (12 + W + 2) * N + (1 << 30)
         try:
@@ -142,7 +148,7 @@ def main():
     # the outer step read (theta, theta_local, peer codes) | momentum and the stage-1 codes | the
     # stage-2 codes - so that no kernel writes near what it reads.
     spread = None
-    if cfg in (0, 1) and args.spread and not args.no_arena:
+    if (sharded or (cfg in (0, 1) and args.spread)) and not args.no_arena:
         from paper_2412_01152_amd.arena import Arena
         try:
             arena = Arena(dev)
@@ -309,13 +315,14 @@ def main():
                              off, N, T, W, alloc)
     dominant = max(names, key=lambda n: kernels[n]["avg_ms"])
     achieved = kernels[dominant]["GB/s"]
-    traffic = measured_traffic_bytes(dominant) if cfg == 2 else None
+    traffic = measured_traffic_bytes(dominant) if cfg == 2 and not sharded else None
     result = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config{cfg}: 10B-shaped parameter set, {N} fp32 elements in {T} tensors, "
                                f"W={W} coded peers, delta={kind}, lr={LR}, momentum={BETA}"
+                   + (f"; shard 1/{args.shard} of every tensor" if sharded else "")
                    if cfg == 2 else f"config{cfg}: N={N} T={T} W={W} delta={kind}",
                    "elements": N, "segments": T, "peers": W, "bytes_per_element_per_step": sum(STAGE_BYTES.values())},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
