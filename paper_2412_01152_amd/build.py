@@ -11,6 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libdiloco_mi355.so")
+EXAMPLE = os.path.join(HERE, "example_outer_sync")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -51,7 +52,18 @@ def build(verbose: bool = False) -> str:
     objs = [os.path.join(BUILD, u[0]) for u in UNITS]
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]
     subprocess.run(cmd, check=True)
+    build_example()
     return OUT
+
+
+def build_example() -> str:
+    """The plain-C caller of the ABI (csrc/example_outer_sync.c), linked against the library just built."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c99", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__",
+           f"-I{rocm}/include", os.path.join(CSRC, "example_outer_sync.c"), f"-L{HERE}", "-ldiloco_mi355",
+           f"-L{rocm}/lib", "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{rocm}/lib", "-o", EXAMPLE]
+    subprocess.run(cmd, check=True)
+    return EXAMPLE
 
 
 if __name__ == "__main__":
