@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--arena-shift", type=int, default=None, metavar="GIB",
                     help="config 2: carve the state at this shift of the arena instead of timing the outer step "
                          "on the candidates (profiling runs: keeps the probes out of the kernel statistics)")
-    ap.add_argument("--cpu-layers", type=int, default=4,
+    ap.add_argument("--cpu-layers", type=int, default=8,
                     help="decoder layers in the CPU-oracle sample (218,112,000 elements each)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
