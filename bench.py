@@ -747,6 +747,13 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
                      "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
         log(f"[bench] extra {name:52s} {ms:8.3f} ms  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:.1f}% of peak")
 
+    # the compute units' own ceiling for stage 2 (table look-ups, bucket arithmetic, LDS bins): the same
+    # call with ONE code buffer standing in for all W contributions, so that HBM delivers 2 bytes per
+    # element instead of 2W + 1 while every instruction is still executed; GB/s counts the real call's bytes
+    timed(f"stage2 W={W}, one buffer passed {W} times: compute ceiling", 2 * W + 1,
+          lambda: B.reduce_chunk([peer_codes[0]] * W, peer_luts, off, W, codes_out=codes2, lut_out=lut2,
+                                 qparams_out=qp, workspace=ws))
+    B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
     local_bf16 = alloc(N, torch.bfloat16).copy_(local)
     scratch_f32 = alloc(N, torch.float32)
     timed("stage1 bf16 theta_local (13 B/elem)", 13,
