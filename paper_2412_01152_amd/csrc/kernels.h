@@ -381,7 +381,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
     unsigned long long* const s_bin = s_bin_all + (tid & (kCopies - 1));   // this lane's copy
     const uint32_t phase = work.phase;
     // Bins and totals live across the block's chunks for as long as the segment stays the same: the
-    // LDS bins are drained into registers before their 40-bit field can overflow, and the registers
+    // LDS bins are drained into registers before either of their fields can overflow, and the registers
     // go to the segment's global bins when the segment changes and when the block leaves.
     uint32_t cur = kNoSegment;
     BinScale bs = bin_scale(0.0f, 0.0f);
