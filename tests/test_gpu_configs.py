@@ -3,7 +3,8 @@
 Configurations 0 and 1 run at their full size, element by element.  Configuration 2 (the one
 bench.py times: 10,211,381,248 elements, 381 tensors, W = 4) runs at full size in the benchmark's
 launch configuration and is checked on sampled tensors the oracle can process whole, plus
-properties that hold at any size.  Configurations 3 and 4 keep their structure (14 heavy-tailed
+properties that hold at any size; so are the call variants bench.py --extras times (bf16
+theta_local, stored accumulation, outer step from fp32 and with the new weights handed back).  Configurations 3 and 4 keep their structure (14 heavy-tailed
 coded peers with the accumulation stored over theta_local; 14 ring chunks of a size that is not a
 multiple of anything, 13 coded peers + un-quantised local addend, bf16 theta_local) on the first
 attention block's tensors, a size the oracle finishes in seconds, and also run at full size: the
@@ -274,6 +275,109 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
     g = lut2[0][codes2[a:b].long()]
     assert torch.equal(mom[a:b], g)
     say(f"[config2] stage 3 checked; total one-bucket flips on sampled tensors: {flips}")
+
+
+# ---------------------------------------------------------------------------------------------
+# the call variants bench.py --extras times, at the same full size: bf16 theta_local in stage 1,
+# stage 2 storing its fp32 accumulation, the outer step from that fp32 array with the workers' new
+# weights handed back in the same pass (fp32, then bf16 from codes); sampled tensors + any-size properties
+# ---------------------------------------------------------------------------------------------
+
+def test_config2_fullsize_call_variants_sampled(B, oracle_mod):
+    sizes = synth.config_segment_sizes(2)
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 4
+    free, _ = torch.cuda.mem_get_info()
+    if free < 215e9:
+        pytest.skip(f"needs about 210 GB of free HBM, have {free / 1e9:.0f} GB")
+    # layer 5 wv (4.2M), layer 33 wo (16.8M), layer 12 attn_norm (4,096), layer 26 w_up (58.7M)
+    sample = [1 + 9 * 5 + 2, 1 + 9 * 33 + 3, 1 + 9 * 12 + 7, 1 + 9 * 26 + 5]
+    say(f"[variants] N={N}; sampled tensors {sample} sizes {[sizes[s] for s in sample]}")
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local16 = torch.empty(N, dtype=torch.bfloat16, device=DEV)
+    acc = torch.empty(N, dtype=torch.float32, device=DEV)          # also the scratch the fills go through
+    peer_codes = [torch.empty(N, dtype=torch.uint8, device=DEV) for _ in range(W)]
+    peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=DEV) for _ in range(W)]
+    qp = B.new_qparams(T, DEV)
+    ws = B.new_workspace(T, DEV)
+    th_s = {s: t2n(theta[off[s]:off[s + 1]]) for s in sample}
+    o1 = {s: [] for s in sample}
+    flips = 0
+    for p in range(W):
+        synth.fill_theta_local(local16, theta, p, "mixture")       # bf16(theta + delta)
+        B.pseudograd_quantize(theta, local16, off, codes_out=peer_codes[p], lut_out=peer_luts[p],
+                              qparams_out=qp, workspace=ws)
+        torch.cuda.synchronize()
+        g_qp = B.qparams_to_numpy(qp)
+        assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
+        for s in sample:
+            a, b = off[s], off[s + 1]
+            o = oracle_mod.pseudograd_quantize(th_s[s], bf16_bits(local16[a:b]), [0, b - a], local_is_bf16=True)
+            check_qparams(g_qp[s:s + 1], o[2])
+            flips += check_codes(t2n(peer_codes[p][a:b]), o[0], o[3], [0, b - a], o[2])
+            check_luts(t2n(peer_luts[p][s]), o[1], o[0], [0, b - a], o[2])
+            o1[s].append(o)
+            peer_codes[p][a:b].copy_(torch.from_numpy(o[0]))        # stage-isolated: the oracle's codes go on
+            peer_luts[p][s].copy_(torch.from_numpy(o[1][0]))
+    say(f"[variants] stage 1 with bf16 theta_local checked for {W} workers")
+    del local16
+    torch.cuda.empty_cache()
+
+    codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
+    lut2 = torch.empty((T, 256), dtype=torch.float32, device=DEV)
+    B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=acc, codes_out=codes2, lut_out=lut2, qparams_out=qp,
+                   workspace=ws)
+    torch.cuda.synchronize()
+    g_qp = B.qparams_to_numpy(qp)
+    assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
+    o_accs = {}
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[0] for o in o1[s]], [o[1] for o in o1[s]], [0, b - a], W)
+        check_qparams(g_qp[s:s + 1], o_q2)
+        flips += check_codes(t2n(codes2[a:b]), o_c2, o_acc, [0, b - a], o_q2)
+        check_luts(t2n(lut2[s]), o_l2, o_c2, [0, b - a], o_q2)
+        assert np.array_equal(t2n(acc[a:b]), o_acc)                 # a fixed sequence of fp32 operations
+        o_accs[s] = (o_acc, o_c2, o_l2)
+        codes2[a:b].copy_(torch.from_numpy(o_c2))                   # stage-isolated, as above
+        lut2[s].copy_(torch.from_numpy(o_l2[0]))
+    del peer_codes
+    torch.cuda.empty_cache()
+    say("[variants] stage 2 storing the accumulation checked")
+
+    # outer step from the stored fp32 average, new weights handed back in fp32
+    mom = torch.zeros(N, dtype=torch.float32, device=DEV)
+    handback = torch.empty(N, dtype=torch.float32, device=DEV)
+    B.outer_step(theta, mom, LR, BETA, delta_fp32=acc, theta_local_out=handback, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(handback, theta) and torch.equal(mom, acc)    # any size: first step, m' = g
+    th1 = {}
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        th_o, m_o = th_s[s].copy(), np.zeros(b - a, dtype=np.float32)
+        oracle_mod.outer_step(th_o, m_o, LR, BETA, delta_fp32=o_accs[s][0])
+        check_outer(t2n(mom[a:b]), m_o, np.zeros(b - a, dtype=np.float32), np.abs(m_o), "momentum")
+        check_outer(t2n(theta[a:b]), th_o, th_s[s], LR * (1 + BETA) * np.abs(m_o), "theta")
+        th1[s] = (th_o, m_o)                                        # the oracle's state goes on, on both sides
+        theta[a:b].copy_(torch.from_numpy(th_o))
+        mom[a:b].copy_(torch.from_numpy(m_o))
+    del handback
+    torch.cuda.empty_cache()
+    # a second step, from the codes, new weights handed back in bf16
+    handback16 = torch.empty(N, dtype=torch.bfloat16, device=DEV)
+    B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off,
+                 theta_local_out=handback16, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(handback16, theta.to(torch.bfloat16))         # any size: round to nearest even
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        th_o, m_o = th1[s][0].copy(), th1[s][1].copy()
+        o_c2, o_l2 = o_accs[s][1], o_accs[s][2]
+        g = o_l2[0][o_c2]
+        oracle_mod.outer_step(th_o, m_o, LR, BETA, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=[0, b - a])
+        check_outer(t2n(mom[a:b]), m_o, th1[s][1], np.abs(g), "momentum, second step")
+        check_outer(t2n(theta[a:b]), th_o, th1[s][0], LR * (np.abs(g) + BETA * np.abs(m_o)), "theta, second step")
+    say(f"[variants] outer step from fp32 and from codes with hand-back checked; flips on sampled tensors: {flips}")
 
 
 # ---------------------------------------------------------------------------------------------
