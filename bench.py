@@ -149,14 +149,15 @@ def main():
     # stage-2 codes - so that no kernel writes near what it reads.
     spread = None
     if (sharded or (cfg in (0, 1) and args.spread)) and not args.no_arena:
-        from paper_2412_01152_amd.arena import Arena
+        from paper_2412_01152_amd.arena import Arena, role_bases
         try:
             arena = Arena(dev)
             if arena.nbytes < (210 << 30):
                 raise RuntimeError(f"arena of {arena.nbytes >> 30} GiB is too small to spread over")
-            spread = {"read": 4 << 30, "state": 104 << 30, "out": 204 << 30}
+            spread = role_bases(arena)
             shift = spread["read"]
-            log(f"[bench] arena of {arena.nbytes >> 30} GiB, buffers spread at +4 / +104 / +204 GiB")
+            log(f"[bench] arena of {arena.nbytes >> 30} GiB, buffers spread at "
+                + " / ".join(f"+{v / (1 << 30):.0f}" for v in spread.values()) + " GiB")
         except RuntimeError as e:
             log(f"[bench] no arena ({e}); one allocation per buffer")
             arena = None

@@ -48,6 +48,21 @@ class Arena:
         return self.buf[start:start + nbytes].view(dtype)
 
 
+def role_bases(arena: Arena) -> Dict[str, int]:
+    """Where small buffers go so that no kernel writes near what it reads: three groups 100 GiB
+    apart, at +4, +104 and +204 GiB (beyond the 96 GiB at which the measured dependence on distance
+    levels off), or a third of the arena apart when the arena is smaller than that needs.
+      "read"   what stage 1, stage 2 and the outer step only read from: theta (also updated in place),
+               theta_local, the peers' codes
+      "state"  momentum and the codes stage 1 writes
+      "out"    the codes stage 2 writes (and the outer step reads)
+    Offsets in bytes into the arena; carve with carve(..., at=base) for the first buffer of a group."""
+    third = arena.nbytes // 3 // ALIGN * ALIGN
+    gap = 100 * GiB if arena.nbytes >= 216 * GiB else third       # the spacing that was measured, if it fits
+    lead = min(4 * GiB, third // 8) // ALIGN * ALIGN
+    return {"read": lead, "state": lead + gap, "out": lead + 2 * gap}
+
+
 def place_outer_state(arena: Arena, N: int, seg_offsets: Sequence[int], shifts_gib: Sequence[int],
                       tail_bytes: int, log=None) -> int:
     """Times, for every candidate shift s, the two kernels whose speed depends on where the state lies

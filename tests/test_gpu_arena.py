@@ -54,3 +54,15 @@ def test_place_outer_state_returns_a_candidate_and_library_works_on_carved_views
     g = torch.cat([got[1][s][got[0][off[s]:off[s + 1]].long()] for s in range(2)])
     assert torch.equal(mom, g)                                             # first step from zero: m' = g
     assert torch.allclose(theta, th0 - 0.7 * 1.9 * g, rtol=1e-5, atol=1e-7)
+
+
+def test_role_bases_are_a_third_of_the_arena_apart():
+    from paper_2412_01152_amd.arena import ALIGN, GiB, Arena, role_bases
+    arena = Arena(DEV, nbytes=3 * GiB)
+    r = role_bases(arena)
+    assert list(r) == ["read", "state", "out"] and all(v % ALIGN == 0 for v in r.values())
+    assert r["state"] - r["read"] == r["out"] - r["state"] == GiB
+    a = arena.carve(1000, torch.float32, at=r["read"])
+    b = arena.carve(1000, torch.float32, at=r["state"])
+    c = arena.carve(1000, torch.uint8, at=r["out"])
+    assert b.data_ptr() - a.data_ptr() == GiB and c.data_ptr() - b.data_ptr() == GiB
