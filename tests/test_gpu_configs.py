@@ -278,6 +278,53 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
 
 
 # ---------------------------------------------------------------------------------------------
+# the whole 10B buffer as ONE quantisation group (every block's sums go to the same accumulators,
+# counts beyond 2^32): properties that hold at any size, against fp64 reductions done by torch
+# ---------------------------------------------------------------------------------------------
+
+def test_fullsize_single_group_properties(B):
+    N = synth.offsets_from_sizes(synth.config_segment_sizes(2))[-1]
+    free, _ = torch.cuda.mem_get_info()
+    if free < 110e9:
+        pytest.skip(f"needs about 105 GB of free HBM, have {free / 1e9:.0f} GB")
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local = synth.fill_theta_local(torch.empty(N, dtype=torch.float32, device=DEV), theta, 0, "mixture")
+    codes, lut, qp = B.pseudograd_quantize(theta, local, [0, N])
+    torch.cuda.synchronize()
+    q = B.qparams_to_numpy(qp)[0]
+    assert int(q["n"]) == N and int(q["status"]) == 0
+    # statistics in fp64, chunk by chunk (two passes, as the definition has it)
+    step = 1 << 28
+    tot = 0.0
+    for a in range(0, N, step):
+        tot += float((theta[a:a + step] - local[a:a + step]).double().sum())
+    mean = tot / N
+    ss = 0.0
+    for a in range(0, N, step):
+        ss += float(((theta[a:a + step] - local[a:a + step]).double() - mean).pow(2).sum())
+    std = (ss / (N - 1)) ** 0.5
+    assert abs(q["mean"] - mean) <= 1e-9 * std and abs(q["std"] - std) <= 1e-9 * std
+    assert abs(float(q["lo"]) - (mean - 6 * std)) <= 1e-6 * std
+    assert abs(float(q["inv_w"]) - 256 / (12 * std)) <= 1e-6 * 256 / (12 * std)
+    # codes: every element in the bucket the returned range gives it; decoding keeps the sum
+    lo, inv_w = torch.tensor(q["lo"], device=DEV), torch.tensor(q["inv_w"], device=DEV)
+    hist = torch.zeros(256, dtype=torch.int64, device=DEV)
+    dec_sum = 0.0
+    abs_sum = 0.0
+    for a in range(0, N, step):
+        d = theta[a:a + step] - local[a:a + step]
+        k = ((d - lo) * inv_w).floor_().clamp_(0, 255).to(torch.uint8)
+        assert torch.equal(k, codes[a:a + step])
+        hist += torch.bincount(k.long(), minlength=256)
+        dec_sum += float(lut[0][k.long()].double().sum())
+        abs_sum += float(d.double().abs().sum())
+        del d, k
+    assert int(hist.sum()) == N and int(hist.min()) > 0
+    assert abs(dec_sum - tot) <= 2 ** -22 * abs_sum
+    say(f"[single group] N={N}: mean {mean:.3e} std {std:.3e}, busiest bucket holds {int(hist.max())} elements")
+
+
+# ---------------------------------------------------------------------------------------------
 # the call variants bench.py --extras times, at the same full size: bf16 theta_local in stage 1,
 # stage 2 storing its fp32 accumulation, the outer step from that fp32 array with the workers' new
 # weights handed back in the same pass (fp32, then bf16 from codes); sampled tensors + any-size properties
