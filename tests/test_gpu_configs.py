@@ -325,6 +325,66 @@ def test_fullsize_single_group_properties(B):
 
 
 # ---------------------------------------------------------------------------------------------
+# stage 2 and two outer steps over the whole 10B buffer (381 tensors, W = 4), EVERY element against
+# the same arithmetic done by torch's elementwise fp32 operations
+# ---------------------------------------------------------------------------------------------
+
+def test_fullsize_reduce_and_outer_every_element(B):
+    sizes = synth.config_segment_sizes(2)
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 4
+    free, _ = torch.cuda.mem_get_info()
+    if free < 190e9:
+        pytest.skip(f"needs about 185 GB of free HBM, have {free / 1e9:.0f} GB")
+    peers = [synth.fill_coded_contribution(torch.empty(N, dtype=torch.uint8, device=DEV), p) for p in range(W)]
+    luts = [synth.synthetic_codebooks(T, p, device=DEV) for p in range(W)]
+    acc = torch.empty(N, dtype=torch.float32, device=DEV)
+    codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
+    ws = B.new_workspace(T, DEV)
+    _, lut2, qp = B.reduce_chunk(peers, luts, off, W, acc_out=acc, codes_out=codes2, workspace=ws)
+    torch.cuda.synchronize()
+    q = B.qparams_to_numpy(qp)
+    assert int(q["n"].sum()) == N and np.all(q["status"] == 0)
+    step = 1 << 27
+
+    def pieces():
+        for s in range(T):
+            for a in range(off[s], off[s + 1], step):
+                yield s, a, min(a + step, off[s + 1])
+
+    for s, a, b in pieces():
+        r = luts[0][s][peers[0][a:b].long()]
+        for p in range(1, W):
+            r = r + luts[p][s][peers[p][a:b].long()]                # fp32, in contribution order
+        r = r * 0.25
+        assert torch.equal(acc[a:b], r), f"tensor {s}: stored accumulation"
+        k = ((r - float(q["lo"][s])) * float(q["inv_w"][s])).floor_().clamp_(0, 255).to(torch.uint8)
+        assert torch.equal(codes2[a:b], k), f"tensor {s}: codes"
+    del peers
+    torch.cuda.empty_cache()
+    say("[every element] stage 2: accumulation and codes equal torch's on all elements")
+
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    mom = torch.zeros(N, dtype=torch.float32, device=DEV)
+    for _ in range(2):
+        B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off, workspace=ws)
+    torch.cuda.synchronize()
+    theta0 = synth.fill_theta_outer(acc)                             # the same seeded values again
+    worst = 0.0
+    for s, a, b in pieces():
+        g = lut2[s][codes2[a:b].long()].double()
+        m1 = g
+        t1 = theta0[a:b].double() - LR * (g + BETA * m1)
+        m2 = BETA * m1 + g
+        t2 = t1 - LR * (g + BETA * m2)
+        scale = torch.maximum(t2.abs(), LR * (1 + BETA) * g.abs() * 2)
+        worst = max(worst, float(((theta[a:b].double() - t2).abs() / scale.clamp_min(1e-300)).max()),
+                    float(((mom[a:b].double() - m2).abs() / m2.abs().clamp_min(1e-300)).max()))
+    assert worst <= 1e-5, worst
+    say(f"[every element] two outer steps: worst relative deviation {worst:.2e}")
+
+
+# ---------------------------------------------------------------------------------------------
 # the call variants bench.py --extras times, at the same full size: bf16 theta_local in stage 1,
 # stage 2 storing its fp32 accumulation, the outer step from that fp32 array with the workers' new
 # weights handed back in the same pass (fp32, then bf16 from codes); sampled tensors + any-size properties
