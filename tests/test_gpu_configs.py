@@ -309,6 +309,7 @@ def test_fullsize_single_group_properties(B):
     # codes: every element in the bucket the returned range gives it; decoding keeps the sum
     lo, inv_w = torch.tensor(q["lo"], device=DEV), torch.tensor(q["inv_w"], device=DEV)
     hist = torch.zeros(256, dtype=torch.int64, device=DEV)
+    bucket_sum = torch.zeros(256, dtype=torch.float64, device=DEV)
     dec_sum = 0.0
     abs_sum = 0.0
     for a in range(0, N, step):
@@ -316,11 +317,16 @@ def test_fullsize_single_group_properties(B):
         k = ((d - lo) * inv_w).floor_().clamp_(0, 255).to(torch.uint8)
         assert torch.equal(k, codes[a:a + step])
         hist += torch.bincount(k.long(), minlength=256)
+        bucket_sum += torch.bincount(k.long(), weights=d.double(), minlength=256)
         dec_sum += float(lut[0][k.long()].double().sum())
         abs_sum += float(d.double().abs().sum())
         del d, k
     assert int(hist.sum()) == N and int(hist.min()) > 0
     assert abs(dec_sum - tot) <= 2 ** -22 * abs_sum
+    # the codebook: every bucket's average, within the per-call bar
+    means = (bucket_sum / hist.double()).cpu().numpy()
+    w = 12 * std / 256
+    assert np.all(np.abs(t2n(lut[0]).astype(np.float64) - means) <= 1e-6 * np.maximum(np.abs(means), w))
     say(f"[single group] N={N}: mean {mean:.3e} std {std:.3e}, busiest bucket holds {int(hist.max())} elements")
 
 
