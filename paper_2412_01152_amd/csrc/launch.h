@@ -92,6 +92,11 @@ constexpr uint64_t kChunkItersReduceWrite = 16;
 // source, which does not stage, 8.54 ms with the 6 that fit, 8.35 with 4).  The reduce-source
 // kernels are fastest with all the blocks their LDS use admits (3 or 4): their table look-ups need
 // the waves.
+// Pass A of the reduce when it also stores the fp32 accumulation: a write stream next to W byte
+// streams wants few blocks while the table look-ups still find enough waves (10B buffer, 4 blocks
+// resident: W = 4: 14.0 ms with all of them, 13.4 with 2; W = 8: 20.5 / 19.4; W = 10: 24.1 with 4,
+// 23.7 with 3, 28.7 with 2; W = 14: 30.8 with the 3 that fit, 38.8 with 2).
+inline int blocks_per_cu_store_acc(uint32_t W) { return W <= 8 ? 2 : 3; }
 constexpr int kBlocksPerCuStreamRead = 1;
 constexpr int kBlocksPerCuStreamWrite = 4;
 constexpr int kBlocksPerCuOuter = 2;

@@ -2,6 +2,8 @@
 // time with -DDILOCO_W_GROUP=0..3 : W in {0..4}, {5..8}, {9..12}, {13..16}.  W is a template
 // argument so that all W code-stream loads of an iteration are in flight together and the W
 // codebooks sit at fixed LDS offsets.
+#include <algorithm>
+
 #include "kernels.h"
 #include "launch.h"
 
@@ -35,7 +37,9 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     constexpr auto kernel = stats_kernel<Src, kWriteAcc>;
     const uint32_t phase = acc_out ? host_phase(acc_out, 4)
                                    : (W > 0 ? host_phase(a.codes[0], 1) : host_phase(a.local, 4));
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 0, phase,
+    int bpc = resident_blocks_per_cu<kernel>();
+    if (kWriteAcc) bpc = std::min(bpc, blocks_per_cu_store_acc(W));
+    Grid g = plan_grid(p.N, p.num_cus, bpc, p.counters + 0, phase,
                        kWriteAcc ? chunk_iters_store_acc(W, kLocal) : kChunkItersRead);
     (void)mark(0, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
