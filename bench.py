@@ -65,6 +65,9 @@ def main():
                     help="quantiser: error of the 8-bit code for other clipping widths, the midpoint codebook and "
                          "per-row groups, on one decoder layer; ring: error and time of the per-hop ring reduce (requantised at every hop) against the "
                          "one-shot W-way reduce, on one decoder layer (config 1's shape)")
+    ap.add_argument("--compute-ceiling", action="store_true",
+                    help="config 2: also time stage 2 with ONE code buffer standing in for all W contributions "
+                         "(every instruction executed, a quarter of the HBM reads): the compute units' own ceiling")
     ap.add_argument("--graph", action="store_true",
                     help="configs 0-2: also record the step into a HIP graph and time its replays")
     ap.add_argument("--shard", type=int, default=1, metavar="K",
@@ -310,6 +313,27 @@ def main():
     copy_ref = measure_copy_kernel(torch, local, alloc)
     log(f"[bench] plain copy kernel ({copy_ref['what']}): {copy_ref['GB/s']:.1f} GB/s; "
         f"step runs at {100 * value / copy_ref['GB/s']:.1f}% of it")
+    ceiling = None
+    if args.compute_ceiling:
+        # table look-ups, bucket arithmetic and LDS bins at full rate while HBM delivers 2 bytes per element
+        # instead of 2W + 1; GB/s counts the real call's bytes
+        def aliased():
+            B.reduce_chunk([peer_codes[0]] * W, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp,
+                           workspace=ws)
+        aliased()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            aliased()
+        e1.record()
+        torch.cuda.synchronize()
+        c_ms = e0.elapsed_time(e1) / 5
+        ceiling = {"stage2_ms": round(c_ms, 3), "GB/s": round((2 * W + 1) * N / (c_ms * 1e-3) / 1e9, 1),
+                   "what": f"int8_reduce_chunk with one code buffer passed {W} times"}
+        log(f"[bench] stage 2 compute ceiling: {c_ms:.3f} ms per call ({ceiling['GB/s']:.1f} GB/s of the real call's "
+            f"bytes, {100 * ceiling['GB/s'] / HBM_PEAK_GBS:.1f}% of the HBM peak)")
+        B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
     extras = None
     if args.extras:
         extras = time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws,
@@ -331,7 +355,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": KERNEL_BYTES[dominant] * N},
-        "kernels": kernels, "stages": stages, "extras": extras, "graph": graph,
+        "kernels": kernels, "stages": stages, "extras": extras, "graph": graph, "stage2_compute_ceiling": ceiling,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(result), flush=True)
@@ -748,13 +772,6 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
                      "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
         log(f"[bench] extra {name:52s} {ms:8.3f} ms  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:.1f}% of peak")
 
-    # the compute units' own ceiling for stage 2 (table look-ups, bucket arithmetic, LDS bins): the same
-    # call with ONE code buffer standing in for all W contributions, so that HBM delivers 2 bytes per
-    # element instead of 2W + 1 while every instruction is still executed; GB/s counts the real call's bytes
-    timed(f"stage2 W={W}, one buffer passed {W} times: compute ceiling", 2 * W + 1,
-          lambda: B.reduce_chunk([peer_codes[0]] * W, peer_luts, off, W, codes_out=codes2, lut_out=lut2,
-                                 qparams_out=qp, workspace=ws))
-    B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
     local_bf16 = alloc(N, torch.bfloat16).copy_(local)
     scratch_f32 = alloc(N, torch.float32)
     timed("stage1 bf16 theta_local (13 B/elem)", 13,
