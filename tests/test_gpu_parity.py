@@ -197,6 +197,42 @@ def test_stage2_all_w(B, oracle_mod, W):
     _run_stage2(B, oracle_mod, off, st, W, divisor=W, with_acc=True)
 
 
+def test_segment_count_at_the_limit(B, oracle_mod):
+    """65,536 quantisation groups (the largest T the library takes) of 0 .. 96 elements - empty ones,
+    single values, a few hundred blocks' worth of segment changes per chunk - through all three calls."""
+    T, W = 65_536, 3
+    rng = np.random.default_rng(20241201)
+    sizes = rng.integers(0, 97, size=T).tolist()
+    sizes[5], sizes[77], sizes[T - 1] = 0, 1, 1
+    theta, off, st = _oracle_peers(oracle_mod, sizes, W)
+    n = off[-1]
+    say(f"[limit] T={T} n={n}")
+    assert B.workspace_bytes(T) > 0
+    # stage 1 on worker 0's inputs
+    _, locals_, _ = synth.make_inputs(sizes, 1, device="cpu")
+    _check_stage1(B, oracle_mod, theta.to(DEV), locals_[0].to(DEV), off, "limit")
+    # stage 2, both forms
+    _run_stage2(B, oracle_mod, off, st, W, divisor=W)
+    _run_stage2(B, oracle_mod, off, st, W, divisor=W, with_acc=True)
+    # stage 3 from the oracle's reduced codes
+    _, o_c2, o_l2, _ = oracle_mod.reduce([s_[0] for s_ in st], [s_[1] for s_ in st], off, W)
+    th_o = theta.numpy().copy()
+    m_o = (np.random.default_rng(7).standard_normal(n) * 1e-3).astype(np.float32)
+    th_t, m_t = torch.from_numpy(th_o).to(DEV), torch.from_numpy(m_o).to(DEV)
+    old_th, old_m = th_o.copy(), m_o.copy()
+    B.outer_step(th_t, m_t, 0.7, 0.9, delta_codes=torch.from_numpy(o_c2).to(DEV),
+                 delta_lut=torch.from_numpy(o_l2).to(DEV), seg_offsets=off)
+    oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=off)
+    torch.cuda.synchronize()
+    so = np.asarray(off)
+    g = np.concatenate([o_l2[k][o_c2[so[k]:so[k + 1]]] for k in range(T)]) if n else np.zeros(0, np.float32)
+    check_outer(t2n(m_t), m_o, old_m, np.abs(g), "momentum")
+    check_outer(t2n(th_t), th_o, old_th, 0.7 * np.abs(g.astype(np.float64) + 0.9 * m_o), "theta")
+    # one more group is refused on the host
+    with pytest.raises(B.DilocoError):
+        B.pseudograd_quantize(theta.to(DEV), locals_[0].to(DEV), off + [n], codes_out=None)
+
+
 @pytest.mark.parametrize("W,divisor", [(0, 1), (0, 3), (1, 2), (4, 5), (13, 14), (16, 17)])
 @pytest.mark.parametrize("alias", [False, True])
 def test_stage2_local_addend(B, oracle_mod, W, divisor, alias):
