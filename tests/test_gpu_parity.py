@@ -405,6 +405,53 @@ def test_nonfinite_input_is_flagged_not_fatal(B, oracle_mod, bad):
     _check_stage1(B, oracle_mod, theta, local, off, "after non-finite")
 
 
+@pytest.mark.parametrize("bad", [float("nan"), float("inf")])
+@pytest.mark.parametrize("materialise", [False, True])
+def test_nonfinite_codebook_entry_in_the_reduce(B, oracle_mod, bad, materialise):
+    """A contribution whose codebook carries a NaN / Inf (its sender's tensor was not finite): the
+    reduce flags that tensor and leaves the others exact; so do the stored accumulation and the outer
+    step taken from the result."""
+    W = 3
+    sizes = [20_000, 5_000, 70_000]
+    theta, off, st = _oracle_peers(oracle_mod, sizes, W)
+    luts1 = st[1][1].copy()
+    busiest = int(np.bincount(st[1][0][off[1]:off[2]], minlength=256).argmax())
+    luts1[1][busiest] = bad                                          # peer 1, tensor 1, its fullest bucket
+    st = [st[0], (st[1][0], luts1, st[1][2], st[1][3]), st[2]]
+    n = off[-1]
+    peer_codes = [torch.from_numpy(s_[0]).to(DEV) for s_ in st]
+    peer_luts = [torch.from_numpy(s_[1]).to(DEV) for s_ in st]
+    acc_t = torch.empty(n, dtype=torch.float32, device=DEV) if materialise else None
+    codes, luts, qp = B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=acc_t)
+    torch.cuda.synchronize()
+    o_acc, o_codes, o_luts, o_qp = oracle_mod.reduce([s_[0] for s_ in st], [s_[1] for s_ in st], off, W)
+    g_qp = B.qparams_to_numpy(qp)
+    assert list(g_qp["status"]) == list(o_qp["status"])
+    assert g_qp["status"][1] & B.STATUS_NONFINITE and g_qp["status"][0] == 0 and g_qp["status"][2] == 0
+    for s in (0, 2):
+        a, b = off[s], off[s + 1]
+        check_qparams(g_qp[s:s + 1], o_qp[s:s + 1])
+        check_codes(t2n(codes[a:b]), o_codes[a:b], o_acc[a:b], [0, b - a], o_qp[s:s + 1])
+        check_luts(t2n(luts[s]), o_luts[s], o_codes[a:b], [0, b - a], o_qp[s:s + 1])
+    if materialise:
+        got = t2n(acc_t)
+        assert np.array_equal(got, o_acc, equal_nan=True)            # the same fp32 operations, NaN where the oracle has NaN
+    # the outer step from the oracle's result: finite tensors move exactly as the oracle's do
+    th_o, m_o = theta.numpy().copy(), np.zeros(n, dtype=np.float32)
+    th_t, m_t = torch.from_numpy(th_o).to(DEV), torch.from_numpy(m_o).to(DEV)
+    B.outer_step(th_t, m_t, 0.7, 0.9, delta_codes=torch.from_numpy(o_codes).to(DEV),
+                 delta_lut=torch.from_numpy(o_luts).to(DEV), seg_offsets=off)
+    oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=o_codes, delta_luts=o_luts, seg_offsets=off)
+    torch.cuda.synchronize()
+    for s in (0, 2):
+        a, b = off[s], off[s + 1]
+        g = o_luts[s][o_codes[a:b]]
+        check_outer(t2n(m_t[a:b]), m_o[a:b], np.zeros(b - a, dtype=np.float32), np.abs(g), "momentum")
+        check_outer(t2n(th_t[a:b]), th_o[a:b], theta.numpy()[a:b], 0.7 * 1.9 * np.abs(g), "theta")
+    a, b = off[1], off[2]
+    assert np.array_equal(np.isfinite(t2n(m_t[a:b])), np.isfinite(m_o[a:b]))
+
+
 def test_large_mean_small_spread(B, oracle_mod):
     """Statistics about a pivot: a pseudo-gradient whose mean is 10^4 standard deviations."""
     sizes = [300_000, 4096]
