@@ -142,7 +142,9 @@ int32_t diloco_pseudograd_quantize(const float* theta_outer, const void* theta_l
  *   acc_out      device, [n] fp32, optional: receives a.  MAY be the same buffer as local_fp32.
  *                When given, a is stored once and read back for the second pass; when NULL, a is
  *                recomputed from the codes in the second pass.
- *   codes_out, lut_out, qparams_out, workspace: as in stage 1.
+ *   codes_out, lut_out, qparams_out, workspace: as in stage 1.  codes_out MAY be the same buffer as
+ *                one of the peer_codes (every element's inputs are read before its code is
+ *                written; that contribution is consumed).
  * The call is a pure function of its inputs: calling it again with a smaller W on the same
  * buffers is the retry of Section 2.4.5.
  */
@@ -197,7 +199,8 @@ int32_t int8_reduce_chunk_variant(const uint8_t* const* peer_codes, const float*
  *   seg_offsets  host, [T+1]; used by the coded form only (may be NULL with T = 0 otherwise)
  *   lr, beta     the paper uses 0.7 and 0.9
  *   theta_local_out  device, [N] fp32 or bf16 (round to nearest even), optional: the new worker
- *                weights, i.e. a copy of theta' (steps 3-4 of Section 2.1's procedure)
+ *                weights, i.e. a copy of theta' (steps 3-4 of Section 2.1's procedure).  In fp32 it
+ *                MAY be the same buffer as delta_fp32 (the average is consumed).
  *   local_dtype  dtype of theta_local_out
  *   workspace    device, 256-byte aligned; required by the coded form (>= diloco_workspace_bytes(T)
  *                bytes); optional for the fp32 form (>= diloco_workspace_bytes(1) bytes, or NULL:

@@ -405,6 +405,40 @@ def test_nonfinite_input_is_flagged_not_fatal(B, oracle_mod, bad):
     _check_stage1(B, oracle_mod, theta, local, off, "after non-finite")
 
 
+@pytest.mark.parametrize("materialise", [False, True])
+def test_outputs_written_over_consumed_inputs(B, oracle_mod, materialise):
+    """codes_out over one contribution's codes, and the fp32 hand-back over the fp32 average."""
+    W = 4
+    sizes = [100_000, 4096, 3, 77_777, 0, 40_001]
+    theta, off, st = _oracle_peers(oracle_mod, sizes, W)
+    n = off[-1]
+    peer_codes = [torch.from_numpy(s_[0]).to(DEV) for s_ in st]
+    peer_luts = [torch.from_numpy(s_[1]).to(DEV) for s_ in st]
+    acc_t = torch.empty(n, dtype=torch.float32, device=DEV)
+    codes, luts, qp = B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=acc_t if materialise else None,
+                                     codes_out=peer_codes[2])
+    torch.cuda.synchronize()
+    assert codes.data_ptr() == peer_codes[2].data_ptr()
+    o_acc, o_codes, o_luts, o_qp = oracle_mod.reduce([s_[0] for s_ in st], [s_[1] for s_ in st], off, W)
+    check_qparams(B.qparams_to_numpy(qp), o_qp)
+    check_codes(t2n(codes), o_codes, o_acc, off, o_qp)
+    check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+    for p in (0, 1, 3):
+        assert np.array_equal(t2n(peer_codes[p]), st[p][0])          # the other contributions are untouched
+    # outer step from the oracle's fp32 average, new weights written over that average
+    delta_t = torch.from_numpy(o_acc).to(DEV)
+    th_o = theta.numpy().copy()
+    m_o = (np.random.default_rng(3).standard_normal(n) * 1e-3).astype(np.float32)
+    th_t, m_t = torch.from_numpy(th_o).to(DEV), torch.from_numpy(m_o).to(DEV)
+    old_th, old_m = th_o.copy(), m_o.copy()
+    B.outer_step(th_t, m_t, 0.7, 0.9, delta_fp32=delta_t, theta_local_out=delta_t)
+    oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_fp32=o_acc)
+    torch.cuda.synchronize()
+    check_outer(t2n(m_t), m_o, old_m, np.abs(o_acc), "momentum")
+    check_outer(t2n(th_t), th_o, old_th, 0.7 * np.abs(o_acc.astype(np.float64) + 0.9 * m_o), "theta")
+    assert torch.equal(delta_t, th_t)
+
+
 @pytest.mark.parametrize("bad", [float("nan"), float("inf")])
 @pytest.mark.parametrize("materialise", [False, True])
 def test_nonfinite_codebook_entry_in_the_reduce(B, oracle_mod, bad, materialise):
