@@ -1,0 +1,131 @@
+"""Seeded random shapes through the three calls: segment sizes around the block-iteration and
+cache-line boundaries (0, 1, 127, 128, 129, 4095, 4096, 4097, ...), views that start a few elements
+into their buffers (a different phase for every stream), any W with or without the fp32 addend, any
+divisor, stored or recomputed accumulation, fp32 or bf16 theta_local, every hand-back form.  Every
+case is compared with the oracle to the per-call bar."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_01152_amd import synth
+from parity_utils import bf16_bits, check_codes, check_luts, check_outer, check_qparams, t2n
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+EDGE_SIZES = [0, 1, 2, 3, 63, 64, 65, 127, 128, 129, 255, 256, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 8192, 8193,
+              32767, 32768, 32769]
+
+
+def _sizes(rng):
+    T = int(rng.integers(1, 13))
+    sizes = []
+    for _ in range(T):
+        r = rng.random()
+        if r < 0.45:
+            sizes.append(int(rng.choice(EDGE_SIZES)))
+        elif r < 0.9:
+            sizes.append(int(rng.integers(1, 150_000)))
+        else:
+            sizes.append(int(rng.integers(150_000, 600_000)))
+    if sum(sizes) == 0:
+        sizes[0] = 5
+    return sizes
+
+
+def _view(rng, host: np.ndarray, dtype=None):
+    """The array on the device, as a view starting 0..7 elements into a larger buffer."""
+    shift = int(rng.integers(0, 8))
+    t = torch.from_numpy(host)
+    if dtype is not None:
+        t = t.view(dtype)
+    buf = torch.empty(t.numel() + 16, dtype=t.dtype, device=DEV)
+    v = buf[shift:shift + t.numel()]
+    v.copy_(t)
+    return v
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shapes(oracle_mod, seed):
+    from paper_2412_01152_amd import binding as B
+    B.load()
+    rng = np.random.default_rng(1000 + seed)
+    sizes = _sizes(rng)
+    W = int(rng.integers(0, 17))
+    has_local = bool(rng.integers(0, 2)) or W == 0
+    divisor = int(rng.choice([1, 2, 3, W + 1, 7, 14, 16, 1000]))
+    bf16_local = bool(rng.integers(0, 2))
+    kind = str(rng.choice(["mixture", "normal", "student_t3"]))
+    n_workers = max(W, 1)
+    theta, locals_, off = synth.make_inputs(sizes, n_workers, kind=kind, device="cpu", seed=synth.BASE_SEED + seed,
+                                            local_dtype=torch.bfloat16 if bf16_local else torch.float32)
+    n, T = off[-1], len(sizes)
+    print(f"[fuzz {seed}] sizes={sizes} W={W} local={has_local} divisor={divisor} bf16={bf16_local} {kind}", flush=True)
+    th_np = theta.numpy()
+
+    # stage 1 for worker 0, on shifted views
+    if bf16_local:
+        l_np = bf16_bits(locals_[0])
+        l_t = _view(rng, l_np.view(np.int16), torch.bfloat16)
+    else:
+        l_np = locals_[0].numpy()
+        l_t = _view(rng, l_np)
+    th_t = _view(rng, th_np)
+    codes_buf = torch.zeros(n + 16, dtype=torch.uint8, device=DEV)
+    cs = int(rng.integers(0, 8))
+    codes, luts, qp = B.pseudograd_quantize(th_t, l_t, off, codes_out=codes_buf[cs:cs + n])
+    torch.cuda.synchronize()
+    o = [oracle_mod.pseudograd_quantize(th_np, bf16_bits(l) if bf16_local else l.numpy(), off, local_is_bf16=bf16_local)
+         for l in locals_]
+    check_qparams(B.qparams_to_numpy(qp), o[0][2])
+    check_codes(t2n(codes), o[0][0], o[0][3], off, o[0][2])
+    check_luts(t2n(luts), o[0][1], o[0][0], off, o[0][2])
+    assert int(codes_buf[:cs].sum()) == 0 and int(codes_buf[cs + n:].sum()) == 0
+
+    # stage 2 from the oracle's contributions
+    local_np = (rng.standard_normal(n) * 1e-3).astype(np.float32) if has_local else None
+    store = bool(rng.integers(0, 2))
+    alias = store and has_local and bool(rng.integers(0, 2))
+    pc = [_view(rng, o[p][0]) for p in range(W)]
+    pl = [torch.from_numpy(o[p][1]).to(DEV) for p in range(W)]
+    local_t = _view(rng, local_np) if has_local else None
+    acc_t = None
+    if store:
+        acc_t = local_t if alias else torch.empty(n + 5, dtype=torch.float32, device=DEV)[5:]
+    codes2, luts2, qp2 = B.reduce_chunk(pc, pl, off, divisor, local_fp32=local_t, acc_out=acc_t)
+    torch.cuda.synchronize()
+    o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[p][0] for p in range(W)], [o[p][1] for p in range(W)], off, divisor,
+                                                local_fp32=local_np)
+    check_qparams(B.qparams_to_numpy(qp2), o_q2)
+    check_codes(t2n(codes2), o_c2, o_acc, off, o_q2)
+    check_luts(t2n(luts2), o_l2, o_c2, off, o_q2)
+    if store:
+        assert np.array_equal(t2n(acc_t), o_acc)
+
+    # stage 3 from the oracle's result, one of the five forms
+    form = int(rng.integers(0, 5))
+    m_np = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    th3, m3 = _view(rng, th_np), _view(rng, m_np)
+    th_o, m_o = th_np.copy(), m_np.copy()
+    out_dtype = {0: None, 1: None, 2: torch.float32, 3: torch.bfloat16, 4: torch.float32}[form]
+    out_t = torch.empty(n + 3, dtype=out_dtype, device=DEV)[3:] if out_dtype is not None else None
+    oname = {None: None, torch.float32: "fp32", torch.bfloat16: "bf16"}[out_dtype]
+    if form in (0, 2, 3):
+        B.outer_step(th3, m3, 0.7, 0.9, delta_codes=_view(rng, o_c2), delta_lut=torch.from_numpy(o_l2).to(DEV),
+                     seg_offsets=off, theta_local_out=out_t)
+        oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=off,
+                                      local_out_dtype=oname)
+        so = np.asarray(off)
+        g = np.concatenate([o_l2[k][o_c2[so[k]:so[k + 1]]] for k in range(T)])
+    else:
+        ws = B.new_workspace(1, DEV) if form == 4 else None
+        B.outer_step(th3, m3, 0.7, 0.9, delta_fp32=_view(rng, o_acc), theta_local_out=out_t, workspace=ws)
+        oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_fp32=o_acc, local_out_dtype=oname)
+        g = o_acc
+    torch.cuda.synchronize()
+    finite = np.isfinite(g)
+    check_outer(t2n(m3)[finite], m_o[finite], m_np[finite], np.abs(g[finite]), "momentum")
+    check_outer(t2n(th3)[finite], th_o[finite], th_np[finite],
+                0.7 * np.abs(g[finite].astype(np.float64) + 0.9 * m_o[finite]), "theta")
+    if out_t is not None:
+        assert torch.equal(out_t, th3.to(out_dtype))
