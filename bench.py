@@ -174,6 +174,12 @@ def main():
                 pass
         return torch.empty(numel, dtype=dtype, device=dev)
 
+    # --extras times stage 1 with a bf16 theta_local as well: that copy of the worker's weights belongs next
+    # to theta like the fp32 one (reads run fastest from the same part of the memory), and the room in
+    # front of theta is free when the state was shifted far enough
+    bf16_slot = None
+    if arena is not None and not spread and args.extras and shift >= 2 * N + 8192:
+        bf16_slot = arena.buf[shift - 2 * N - 4096:shift - 4096].view(torch.bfloat16)
     theta = alloc(N, torch.float32, at=shift if arena is not None else None)
     local = alloc(N, torch.float32)
     if spread:
@@ -337,7 +343,7 @@ def main():
     extras = None
     if args.extras:
         extras = time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws,
-                             off, N, T, W, alloc)
+                             off, N, T, W, alloc, bf16_slot)
     dominant = max(names, key=lambda n: kernels[n]["avg_ms"])
     achieved = kernels[dominant]["GB/s"]
     traffic = measured_traffic_bytes(dominant) if cfg == 2 and not sharded else None
@@ -752,7 +758,7 @@ def bench_config4_overlap(args, np, torch, B, synth, dev):
 
 
 def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws, off, N, T, W,
-                alloc):
+                alloc, bf16_slot=None):
     """Whole-call timings (HIP events around the call, 5 repetitions) of the variants bench's step does
     not use.  Runs last: the stored-accumulation variant overwrites theta_local."""
     out = {}
@@ -772,15 +778,18 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
                      "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
         log(f"[bench] extra {name:52s} {ms:8.3f} ms  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:.1f}% of peak")
 
-    local_bf16 = alloc(N, torch.bfloat16).copy_(local)
+    # the bf16 weights stage 1 READS sit next to theta when there is room (bf16_slot); the bf16 weights the
+    # outer step WRITES go far from theta and momentum, like every written buffer
+    handback_bf16 = alloc(N, torch.bfloat16)
+    local_bf16 = (bf16_slot if bf16_slot is not None else handback_bf16).copy_(local)
     scratch_f32 = alloc(N, torch.float32)
     timed("stage1 bf16 theta_local (13 B/elem)", 13,
           lambda: B.pseudograd_quantize(theta, local_bf16, off, codes_out=codes1, lut_out=lut1, qparams_out=qp,
                                         workspace=ws))
     timed("stage3 coded + bf16 hand-back (19 B/elem)", 19,
           lambda: B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off,
-                               theta_local_out=local_bf16, workspace=ws))
-    del local_bf16
+                               theta_local_out=handback_bf16, workspace=ws))
+    del local_bf16, handback_bf16
     timed(f"stage2 W={W} storing the accumulation ({W + 9} B/elem)", W + 9,
           lambda: B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=local, codes_out=codes2, lut_out=lut2,
                                  qparams_out=qp, workspace=ws))
