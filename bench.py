@@ -626,7 +626,6 @@ def bench_config4(args, np, torch, B, synth, dev):
     synth.fill_theta_local(local, theta, W, "mixture")
     local.sub_(theta).neg_()                      # the owner's own fp32 pseudo-gradient (input preparation)
     torch.cuda.synchronize()
-    del theta
     log(f"[bench] {W} peers ready ({time.time() - t0:.1f}s)")
     qp1 = B.new_qparams(1, dev)
 
@@ -648,6 +647,26 @@ def bench_config4(args, np, torch, B, synth, dev):
     bpe = W + 13
     value = bpe * N / (elapsed / args.steps) / 1e9
     log(f"[bench] 14 chunk calls: {elapsed * 1e3 / args.steps:.3f} ms  {value:.1f} GB/s ({100 * value / HBM_PEAK_GBS:.1f}% of peak)")
+    # then the outer step from the requantised chunks (14 quantisation groups at the odd chunk offsets)
+    outer = None
+    try:
+        mom = alloc(N, torch.float32).zero_()
+    except RuntimeError:
+        mom = None
+    if mom is not None:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=coff, workspace=ws)
+        e0.record()
+        for _ in range(max(1, args.steps)):
+            B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=coff, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        o_ms = e0.elapsed_time(e1) / max(1, args.steps)
+        o_gbs = 17 * N / (o_ms * 1e-3) / 1e9
+        outer = {"ms": round(o_ms, 3), "bytes_per_element": 17, "GB/s": round(o_gbs, 1),
+                 "frac_of_peak": round(o_gbs / HBM_PEAK_GBS, 4)}
+        log(f"[bench] then the outer step from the 14 requantised chunks: {o_ms:.3f} ms  {o_gbs:.1f} GB/s "
+            f"({100 * o_gbs / HBM_PEAK_GBS:.1f}% of peak)")
     result = {"metric": "int8 reduce per ring chunk, 13 coded + fp32 local: GB/s & % HBM peak, 10B",
               "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
               "ms_per_step": round(elapsed * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
@@ -655,7 +674,8 @@ def bench_config4(args, np, torch, B, synth, dev):
               "config": {"workload": f"config4: {N} elements as 14 ring chunks of {chunk_sizes[0]}, 13 coded peers + "
                                      f"fp32 local, divisor 14, one int8_reduce_chunk call per chunk",
                          "elements": N, "segments": 14, "peers": W, "bytes_per_element_per_step": bpe},
-              "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "roofline": None, "cpu_baseline": None}
+              "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "outer_step_after": outer, "roofline": None,
+              "cpu_baseline": None}
     print(json.dumps(result), flush=True)
 
 
