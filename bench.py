@@ -430,8 +430,7 @@ def study_quantiser(args, np, torch, B, synth, dev):
     sizes = synth.config_segment_sizes(1)
     off = synth.offsets_from_sizes(sizes)
     N = off[-1]
-    row_len = [4096, 4096, 4096, 4096, 4096, 4096, 14336, 4096, 4096]       # the inner dimension of each tensor
-    row_sizes = [r for n, r in zip(sizes, row_len) for _ in range(n // r)]
+    row_sizes = synth.layer_row_sizes()                                    # one group per matrix row
     row_off = synth.offsets_from_sizes(row_sizes)
     assert row_off[-1] == N
     theta = torch.empty(N, dtype=torch.float32, device=dev)

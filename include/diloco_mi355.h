@@ -15,8 +15,8 @@
  *
  * General conventions
  *   - "device" pointers are HIP device memory on the current device; "host" pointers are ordinary
- *     host memory.  All buffers are owned by the caller.  The library allocates and frees nothing,
- *     keeps no state between calls, and never synchronises the device.
+ *     host memory.  All buffers are owned by the caller.  The library allocates and frees nothing
+ *     and never synchronises the device.
  *   - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL = the null
  *     stream) and returns.  Host arrays (seg_offsets, pointer tables) are consumed before the call
  *     returns and may be reused at once.  What is enqueued is kernels only - no copies, no memset
@@ -35,13 +35,16 @@
  *     Data-dependent conditions (constant tensor, NaN input, empty segment) never fail a call:
  *     they are reported per segment in diloco_qparams.status.
  *   - Calls that use the same workspace must be ordered on one stream.
- *   - One environment variable is read, at every quantising call: DILOCO_WRITE_PHASE.  The second
- *     pass of diloco_pseudograd_quantize holds its output codes back in on-chip memory and writes
- *     them during a periodic window of the device's constant-rate clock (the first 10 us of every
- *     40 us), which the memory system serves faster than a steady trickle of writes among the
- *     reads; buffers below 2^27 elements are written at once.  DILOCO_WRITE_PHASE=0 writes at once
- *     at every size; DILOCO_WRITE_PHASE=<period_us>,<window_us> sets the timing and applies at
- *     every size.  Results do not depend on it.
+ *   - State.  The library keeps no data between calls: every result is a function of the call's
+ *     arguments.  What it does keep, per process, is (a) the number of resident blocks per compute
+ *     unit of each kernel, looked up once (thread-safe), and (b) two instrumentation settings that
+ *     only the calls at the end of this header change and that never alter results:
+ *     diloco_profile_passes (per host thread) and diloco_tune_write_phase (per process).  No
+ *     environment variable is read.
+ *   - The second pass of diloco_pseudograd_quantize holds its output codes back in on-chip memory
+ *     and writes them during a periodic window of the device's constant-rate clock (the first 10 us
+ *     of every 40 us), which the memory system serves faster than a steady trickle of writes among
+ *     the reads; buffers below 2^27 elements are written at once.
  */
 #ifndef DILOCO_MI355_H
 #define DILOCO_MI355_H
@@ -246,6 +249,19 @@ int32_t diloco_ring_order(const double* bandwidth, uint32_t n, uint32_t* order_o
  * Returns DILOCO_OK.
  */
 int32_t diloco_profile_passes(void* const* events);
+
+/*
+ * Instrumentation for tests and benchmarks (not part of the method): when the second pass of
+ * diloco_pseudograd_quantize writes the codes it holds back on chip.  Process-wide; applies to calls
+ * made after it returns.  Results never depend on it.
+ *     period_us < 0              the built-in choice (by buffer size, see the conventions above)
+ *     period_us == 0             write every iteration's codes at once, at every size
+ *     period_us > 0              hold codes back at EVERY size and write them during the first
+ *                                window_us of every period_us microseconds (or when the on-chip
+ *                                staging area is full); 1 <= window_us <= period_us <= 1,000,000
+ * Returns DILOCO_OK, or DILOCO_ERR_SIZE for a window or period outside those bounds (nothing changes).
+ */
+int32_t diloco_tune_write_phase(int32_t period_us, int32_t window_us);
 
 #ifdef __cplusplus
 }

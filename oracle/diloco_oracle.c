@@ -27,8 +27,8 @@
  *   gets its midpoint;  sigma == 0 gives all codes 0 and lut[0] = mean;  the 1/k division happens
  *   before requantising;  Nesterov in the form  m' = beta*m + g,  theta' = theta - lr*(g + beta*m').
  *
- * Precision: statistics and bucket sums in fp64, plain sequential loops in index order.  The
- * bucket index is taken in fp32 as two separately rounded operations (subtract, multiply) because
+ * Precision: statistics in fp64 (their running sums in long double), bucket sums in fp64, plain
+ * sequential loops in index order.  The bucket index is taken in fp32 as two separately rounded operations (subtract, multiply) because
  * the deployed quantiser works on fp32 tensors; the C compiler must not fuse them
  * (build with -ffp-contract=off).  OpenMP is used only across independent segments or independent
  * elements, so results do not depend on the thread count.
@@ -122,16 +122,20 @@ void oracle_quantize(const float* x, uint64_t n, double range_sigmas, int midpoi
         return;
     }
 
-    /* item 1: mean and standard deviation of the tensor */
-    double sum = 0.0;
-    for (uint64_t i = 0; i < n; ++i) sum += (double)x[i];
-    double mu = sum / (double)n;
-    double sq = 0.0;
+    /* item 1: mean and standard deviation of the tensor, two passes as the definition reads.
+     * The two running sums are kept in long double (64-bit significand on x86): a sequential fp64
+     * sum of n terms drifts by about sqrt(n) * 1e-16 * |mean|, which for a tensor whose mean is
+     * thousands of standard deviations would be visible at the 1e-9 * sigma level the parity
+     * tests hold the mean to.  The results are rounded to fp64 once. */
+    long double sum = 0.0L;
+    for (uint64_t i = 0; i < n; ++i) sum += (long double)x[i];
+    double mu = (double)(sum / (long double)n);
+    long double sq = 0.0L;
     for (uint64_t i = 0; i < n; ++i) {
-        double c = (double)x[i] - mu;
+        long double c = (long double)x[i] - (long double)mu;
         sq += c * c;
     }
-    double sigma = (n > 1) ? sqrt(sq / (double)(n - 1)) : 0.0;
+    double sigma = (n > 1) ? (double)sqrtl(sq / (long double)(n - 1)) : 0.0;
     r.mean = mu;
     r.std = sigma;
     if (!isfinite(mu) || !isfinite(sigma)) r.status |= ORACLE_STATUS_NONFINITE;

@@ -30,7 +30,8 @@ assert QPARAMS_DTYPE.itemsize == QPARAMS_BYTES
 
 EXPORTS = ("diloco_workspace_bytes", "diloco_strerror", "diloco_pseudograd_quantize",
            "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes",
-           "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant", "diloco_ring_order")
+           "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant", "diloco_ring_order",
+           "diloco_tune_write_phase")
 
 CODEBOOK_MEAN, CODEBOOK_MIDPOINT = 0, 1
 
@@ -73,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.outer_nesterov_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u64, f32, f32, vp, i32, vp, sz, vp]
     lib.diloco_profile_passes.restype = i32
     lib.diloco_profile_passes.argtypes = [vp]
+    lib.diloco_tune_write_phase.restype = i32
+    lib.diloco_tune_write_phase.argtypes = [i32, i32]
     _lib = lib
     return lib
 
@@ -86,6 +89,13 @@ def profile_passes(events: Optional[Sequence[int]]) -> None:
     assert len(events) == 4
     arr = (ctypes.c_void_p * 4)(*events)
     lib.diloco_profile_passes(ctypes.cast(arr, ctypes.c_void_p))
+
+
+def tune_write_phase(period_us: int, window_us: int = 0) -> None:
+    """diloco_tune_write_phase: < 0 the built-in choice, 0 write at once, else (period, window) in us."""
+    rc = load().diloco_tune_write_phase(ctypes.c_int32(period_us), ctypes.c_int32(window_us))
+    if rc != 0:
+        raise DilocoError(rc, "diloco_tune_write_phase")
 
 
 def workspace_bytes(T: int) -> int:

@@ -4,8 +4,8 @@
 #include <math.h>
 
 #include <algorithm>
-#include <stdio.h>
-#include <stdlib.h>
+#include <atomic>
+#include <mutex>
 #include <string.h>
 
 #include "finalize_kernels.h"
@@ -56,20 +56,33 @@ int32_t check_segments(const uint64_t* seg, uint32_t T, uint64_t N) {
     return DILOCO_OK;
 }
 
+// Timing of pass B's staged code writes.  The product picks it by size alone (staged from
+// kMinPhasedElems elements on, with the built-in period and window); diloco_tune_write_phase lets a
+// test or a benchmark force another choice.  One packed word, so a reader never sees half an update:
+// bit 63 = override active, bits 32..62 = period in us (0 = write at once), bits 0..31 = window in us.
+std::atomic<uint64_t> g_write_phase_override{0};
+constexpr uint64_t kOverrideActive = 1ull << 63;
+
 // Write window of pass B in ticks of the device's constant-rate clock; period 0 (write at once)
-// when the clock rate cannot be read or DILOCO_WRITE_PHASE=0 is set in the environment.
-WritePhase write_phase_ticks() {
+// when the clock rate cannot be read.
+WritePhase write_phase_ticks(int period_us, int window_us) {
     WritePhase w = {0, 0};
-    const char* env = getenv("DILOCO_WRITE_PHASE");
-    if (env && env[0] == '0') return w;
     int dev = 0, khz = 0;
     if (hipGetDevice(&dev) != hipSuccess) return w;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz < 1000) return w;
-    int period_us = kWritePeriodUs, window_us = kWriteWindowUs;
-    if (env) sscanf(env, "%d,%d", &period_us, &window_us);
     w.period = (uint32_t)((long long)khz * period_us / 1000);
     w.window = (uint32_t)((long long)khz * window_us / 1000);
     return w;
+}
+
+WritePhase choose_write_phase(uint64_t N) {
+    const uint64_t o = g_write_phase_override.load(std::memory_order_relaxed);
+    if (o & kOverrideActive) {
+        const int period_us = (int)((o >> 32) & 0x7fffffffu), window_us = (int)(o & 0xffffffffu);
+        return period_us ? write_phase_ticks(period_us, window_us) : WritePhase{0, 0};
+    }
+    // a launch shorter than a few periods only loses by waiting for its window
+    return N >= kMinPhasedElems ? write_phase_ticks(kWritePeriodUs, kWriteWindowUs) : WritePhase{0, 0};
 }
 
 int32_t num_compute_units(int* out) {
@@ -103,9 +116,7 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     p.stream = stream;
     int32_t rc = num_compute_units(&p.num_cus);
     if (rc) return rc;
-    // a launch shorter than a few periods only loses by waiting for its window (an explicit
-    // DILOCO_WRITE_PHASE=<period>,<window> applies at any size)
-    p.write_phase = (N >= kMinPhasedElems || getenv("DILOCO_WRITE_PHASE")) ? write_phase_ticks() : WritePhase{0, 0};
+    p.write_phase = choose_write_phase(N);
     hipError_t e = upload_offsets(seg_host, T + 1, (uint64_t*)(ws + L.seg), stream);
     if (e != hipSuccess) return (int32_t)e;
     const size_t words = (L.total - L.stats) / sizeof(uint64_t);
@@ -319,6 +330,21 @@ size_t diloco_workspace_bytes(uint32_t T) {
 int32_t diloco_profile_passes(void* const* events) {
     PassEvents& pe = pass_events();
     for (int i = 0; i < 4; ++i) pe.ev[i] = events ? (hipEvent_t)events[i] : nullptr;
+    return DILOCO_OK;
+}
+
+int32_t diloco_tune_write_phase(int32_t period_us, int32_t window_us) {
+    if (period_us < 0) {                                  // back to the built-in choice by size
+        g_write_phase_override.store(0, std::memory_order_relaxed);
+        return DILOCO_OK;
+    }
+    if (period_us == 0) {                                 // write at once, at every size
+        g_write_phase_override.store(kOverrideActive, std::memory_order_relaxed);
+        return DILOCO_OK;
+    }
+    if (window_us < 1 || window_us > period_us || period_us > 1000000) return DILOCO_ERR_SIZE;
+    g_write_phase_override.store(kOverrideActive | ((uint64_t)period_us << 32) | (uint64_t)window_us,
+                                 std::memory_order_relaxed);
     return DILOCO_OK;
 }
 

@@ -245,9 +245,9 @@ struct WorkspaceLayout {
     size_t seg, stats, pivot, hsumq, hcnt, osum, ocnt, counters, total;
 };
 constexpr int kNumCounters = 4;     // chunk counters: pass A, pass B, outer step, spare
-__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-__host__ inline WorkspaceLayout workspace_layout(uint32_t T) {
-    WorkspaceLayout L;
+__host__ __device__ constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+__host__ constexpr WorkspaceLayout workspace_layout(uint32_t T) {
+    WorkspaceLayout L{};
     size_t o = 0;
     L.seg = o;
     o = align_up(o + sizeof(uint64_t) * ((size_t)T + 1), 256);

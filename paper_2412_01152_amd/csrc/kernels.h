@@ -51,7 +51,7 @@ struct SrcPseudoGrad {
                              : ((const float*)theta_local)[i];
         return __fsub_rn(theta_outer[i], b);
     }
-    __device__ __forceinline__ float first_value(uint64_t i, uint32_t) const { return value1(i); }
+    __device__ __forceinline__ float sample_value(uint64_t i, uint32_t) const { return value1(i); }
 };
 
 // A stored fp32 array (second pass of stage 2 when the accumulation was written out).
@@ -72,7 +72,7 @@ struct SrcF32 {
     }
     __device__ __forceinline__ f32x4 value4(const Raw& r) const { return r.a; }
     __device__ __forceinline__ float value1(uint64_t i) const { return x[i]; }
-    __device__ __forceinline__ float first_value(uint64_t i, uint32_t) const { return x[i]; }
+    __device__ __forceinline__ float sample_value(uint64_t i, uint32_t) const { return x[i]; }
 };
 
 // Section 2.2's reduction: decode each of the W coded contributions through its segment's
@@ -145,8 +145,8 @@ struct SrcReduce {
         }
         return finish(acc);
     }
-    // Same value straight from global memory (no LDS tables needed): used for the pivot.
-    __device__ __forceinline__ float first_value(uint64_t i, uint32_t s) const {
+    // Same value straight from global memory (no LDS tables needed): used for the pivot samples.
+    __device__ __forceinline__ float sample_value(uint64_t i, uint32_t s) const {
         float acc = kHasLocal ? local[i] : 0.0f;
 #pragma unroll
         for (int p = 0; p < W; ++p)
@@ -158,17 +158,43 @@ struct SrcReduce {
 // ------------------------------------------------------------------------------------------
 // pass A: statistics (Section 2.2 item 1)
 // ------------------------------------------------------------------------------------------
-// Each thread keeps fp64 sums of (x - c) and (x - c)^2 with c = first value of the segment: the
-// shift removes the cancellation of a large mean and makes a constant segment give exactly 0.
+// Each thread keeps fp64 sums of (x - c) and (x - c)^2 about a pivot c that lies inside the bulk of
+// the segment: the shift removes the cancellation of a large mean and makes a constant segment give
+// exactly 0.  The variance is formed as (S2 - S1^2 / n) / (n - 1), which loses about (D / sigma)^2
+// of fp64 precision when the pivot sits D away from the mean, so the pivot must not be an outlier:
+// it is the median of nine values taken at evenly spread positions of the segment (first, 1/8, ...,
+// last).  For the median to be an outlier at least five of the nine samples would have to be, and
+// values that frequent dominate sigma themselves, so D / sigma stays small either way.
 // The pivots are written by a one-thread-per-segment kernel before the pass starts, because the
 // pass may overwrite its own input (accumulation stored in place over the local addend).
 // One pair of fp64 atomics per (block, segment).  When kWriteAcc, the values are also stored.
+constexpr int kPivotSamples = 9;
 template <class Src>
 __global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t T,
                              float* __restrict__ pivot) {
     uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= T) return;
-    pivot[s] = seg[s + 1] > seg[s] ? src.first_value(seg[s], s) : 0.0f;
+    const uint64_t a = seg[s], n = seg[s + 1] - a;
+    if (n == 0) {
+        pivot[s] = 0.0f;
+        return;
+    }
+    float v[kPivotSamples];
+#pragma unroll
+    for (int j = 0; j < kPivotSamples; ++j)
+        v[j] = src.sample_value(a + (uint64_t)j * (n - 1) / (kPivotSamples - 1), s);
+    // odd-even transposition sort, fully unrolled (a NaN sample drops out: fminf / fmaxf return the
+    // other operand; the statistics pass itself still sees it and the segment is flagged)
+#pragma unroll
+    for (int round = 0; round < kPivotSamples; ++round) {
+#pragma unroll
+        for (int i = round & 1; i + 1 < kPivotSamples; i += 2) {
+            const float lo = fminf(v[i], v[i + 1]), hi = fmaxf(v[i], v[i + 1]);
+            v[i] = lo;
+            v[i + 1] = hi;
+        }
+    }
+    pivot[s] = v[kPivotSamples / 2];
 }
 
 template <class Src, bool kWriteAcc>

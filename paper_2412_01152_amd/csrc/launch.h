@@ -45,16 +45,15 @@ inline hipError_t mark(int which, hipStream_t stream) {
     return e ? hipEventRecord(e, stream) : hipSuccess;
 }
 
-// Resident blocks per compute unit of a kernel, looked up once per process.
+// Resident blocks per compute unit of a kernel, looked up once per process (the initialisation of a
+// function-local static is thread-safe).
 template <auto Kernel>
 inline int resident_blocks_per_cu() {
-    static int occ = 0;
-    if (occ == 0) {
+    static const int occ = [] {
         int v = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, Kernel, kThreads, 0) != hipSuccess || v < 1)
-            v = 4;
-        occ = v;
-    }
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, Kernel, kThreads, 0) != hipSuccess || v < 1) v = 4;
+        return v;
+    }();
     return occ;
 }
 

@@ -39,6 +39,14 @@ def layer_tensor_sizes() -> List[int]:
     return [q, kv, kv, q, ff, ff, ff, HIDDEN, HIDDEN]
 
 
+def layer_row_sizes() -> List[int]:
+    """One decoder layer cut into one quantisation group per matrix row (row = the inner dimension of
+    each weight matrix: 4096 everywhere except w_down's 14336; each norm vector is one row): 43,010
+    groups over the same 218,112,000 elements."""
+    row_len = [HIDDEN, HIDDEN, HIDDEN, HIDDEN, HIDDEN, HIDDEN, FFN, HIDDEN, HIDDEN]
+    return [r for n, r in zip(layer_tensor_sizes(), row_len) for _ in range(n // r)]
+
+
 def model_tensor_sizes(n_layers: int = N_LAYERS) -> List[int]:
     """Element counts of the full untied model: embed, n_layers x layer, final norm, head."""
     sizes = [VOCAB * HIDDEN]
@@ -215,5 +223,6 @@ def n_elements(config: int) -> int:
 
 
 assert sum(layer_tensor_sizes()) == 218_112_000
+assert len(layer_row_sizes()) == 43_010 and sum(layer_row_sizes()) == 218_112_000
 assert sum(model_tensor_sizes()) == 10_211_381_248
 assert math.ceil(10_211_381_248 / 14) == 729_384_375

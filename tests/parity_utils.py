@@ -2,7 +2,8 @@
 
 Codes: byte-equal, except that at most 1e-6 of the elements may differ by exactly one bucket and
 only where the oracle's bucket coordinate sits within 1e-3 of a bucket edge.
-Scales: lo / inv_w within 1e-6 relative; mean (relative to std) and std within 1e-9.
+Scales: lo / inv_w within 1e-6 relative and bit-equal in at least 99 % of the segments (checked where
+there are 100 or more); mean (relative to std) and std within 1e-9.
 Codebook (populated buckets): |diff| <= 1e-6 * max(|lut|, bucket width).
 fp32 accumulations: |diff| <= 1e-6 * max(|a|, sum of |addends| / divisor).
 Outer parameters and momentum: |diff| <= 1e-5 * max(|old|, |new|, lr * |g + beta m'|).
@@ -19,9 +20,12 @@ def bf16_bits(t):
     return np.ascontiguousarray(t.detach().cpu().view(torch.int16).numpy().view(np.uint16))
 
 
-def check_qparams(gpu_qp, orc_qp):
+def check_qparams(gpu_qp, orc_qp, require_exact=None):
+    """Returns the number of segments whose fp32 (lo, inv_w) are bit-equal to the oracle's.  With 100 or
+    more segments at least 99 % of them must be (require_exact overrides the fraction: 1.0 = all)."""
     assert gpu_qp.shape == orc_qp.shape
     exact = 0
+    populated = 0
     for s in range(orc_qp.size):
         g, o = gpu_qp[s], orc_qp[s]
         assert g["n"] == o["n"], f"segment {s}: n {g['n']} vs {o['n']}"
@@ -29,11 +33,16 @@ def check_qparams(gpu_qp, orc_qp):
         sd = max(float(o["std"]), 1e-300)
         if o["n"] == 0:
             continue
-        assert abs(g["mean"] - o["mean"]) <= 1e-9 * sd + 1e-12 * abs(o["mean"]), f"segment {s}: mean"
+        populated += 1
+        assert abs(g["mean"] - o["mean"]) <= 1e-9 * sd, f"segment {s}: mean {g['mean']} vs {o['mean']}"
         assert abs(g["std"] - o["std"]) <= 1e-9 * sd, f"segment {s}: std {g['std']} vs {o['std']}"
         assert abs(float(g["lo"]) - float(o["lo"])) <= 1e-6 * abs(float(o["lo"])) + 1e-300, f"segment {s}: lo"
         assert abs(float(g["inv_w"]) - float(o["inv_w"])) <= 1e-6 * abs(float(o["inv_w"])), f"segment {s}: inv_w"
         exact += int(g["lo"] == o["lo"] and g["inv_w"] == o["inv_w"])
+    if require_exact is None and populated >= 100:
+        require_exact = 0.99
+    if require_exact is not None:
+        assert exact >= require_exact * populated, f"only {exact} of {populated} segments have bit-equal lo / inv_w"
     return exact
 
 

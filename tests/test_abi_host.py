@@ -108,6 +108,18 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert o(vp(0x1001), fake, fake, vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -3
 
 
+def test_write_phase_tuning_validates_its_arguments(lib):
+    """The instrumentation call that retimes pass B's staged code writes: host state only, no device use."""
+    t = lib.diloco_tune_write_phase
+    try:
+        assert t(40, 10) == 0 and t(10, 10) == 0 and t(1000000, 1) == 0
+        assert t(0, 0) == 0 and t(0, 123) == 0                 # write at once: the window is ignored
+        for period, window in ((40, 0), (40, -3), (40, 41), (1000001, 1), (1, 2)):
+            assert t(period, window) == -2
+    finally:
+        assert t(-1, 0) == 0                                   # back to the built-in choice
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     from paper_2412_01152_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

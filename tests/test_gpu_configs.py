@@ -189,9 +189,10 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
     free, _ = torch.cuda.mem_get_info()
     if free < 190e9:
         pytest.skip(f"needs about 185 GB of free HBM, have {free / 1e9:.0f} GB")
-    # sampled tensors: final norm (4,096), layer 7 wk (4.2M), layer 41 wq (16.8M), layer 20 ffn_norm,
-    # layer 3 w_down (58.7M)
-    sample = [T - 2, 1 + 9 * 7 + 1, 1 + 9 * 41 + 0, 1 + 9 * 20 + 8, 1 + 9 * 3 + 6]
+    # sampled tensors: the embedding and the output head (525M elements each: the largest counts and the
+    # longest residency of the blocks in one segment), final norm (4,096), layer 7 wk (4.2M), layer 41 wq
+    # (16.8M), layer 20 ffn_norm, layer 3 w_down (58.7M)
+    sample = [0, T - 1, T - 2, 1 + 9 * 7 + 1, 1 + 9 * 41 + 0, 1 + 9 * 20 + 8, 1 + 9 * 3 + 6]
     say(f"[config2] N={N} T={T}; sampled tensors {sample} sizes {[sizes[s] for s in sample]}")
     theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
     local = torch.empty(N, dtype=torch.float32, device=DEV)
@@ -221,11 +222,11 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
             peer_codes[p][a:b].copy_(torch.from_numpy(o[0]))
             peer_luts[p][s].copy_(torch.from_numpy(o[1][0]))
         say(f"[config2] peer {p}: stage 1 checked on {len(sample)} tensors")
-    # any-size property on the largest tensor (embedding, 525M elements) of peer 0: the codebook
-    # is the bucket mean, so decoding preserves the tensor's sum
-    a, b = off[0], off[1]
+    # any-size property on a tensor outside the sample (layer 0 w_gate, 58.7M elements) of peer 0: the
+    # codebook is the bucket mean, so decoding preserves the tensor's sum
+    a, b = off[5], off[6]
     d64 = (theta[a:b].double() - local[a:b].double())
-    dec = peer_luts[0][0][peer_codes[0][a:b].long()].double()
+    dec = peer_luts[0][5][peer_codes[0][a:b].long()].double()
     assert abs(float(dec.sum() - d64.sum())) <= 2 ** -22 * float(d64.abs().sum())
     assert float((dec - d64).abs().max()) < 1.0                      # finite, no wild decode
     del d64, dec
@@ -251,13 +252,13 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
         lut2[s].copy_(torch.from_numpy(o_l2[0]))
     say("[config2] stage 2 checked")
     # requantisation keeps the sum of the fp32 average it encodes (any size): recompute the average
-    # of the embedding tensor with torch and compare sums
-    a, b = off[0], off[1]
+    # of layer 0's w_gate with torch and compare sums
+    a, b = off[5], off[6]
     acc = torch.zeros(b - a, dtype=torch.float32, device=DEV)
     for p in range(W):
-        acc += peer_luts[p][0][peer_codes[p][a:b].long()]
+        acc += peer_luts[p][5][peer_codes[p][a:b].long()]
     acc *= 0.25
-    dec2 = lut2[0][codes2[a:b].long()]
+    dec2 = lut2[5][codes2[a:b].long()]
     assert abs(float(dec2.double().sum() - acc.double().sum())) <= 2 ** -22 * float(acc.double().abs().sum())
     del acc, dec2
     torch.cuda.empty_cache()
@@ -271,8 +272,8 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
         check_outer(t2n(mom[a:b]), m_o, np.zeros(b - a, dtype=np.float32), np.abs(m_o), "momentum")
         check_outer(t2n(theta[a:b]), th_o, th_s[s], LR * (1 + BETA) * np.abs(m_o), "theta")
     # first step from a zero buffer: m' = g everywhere, theta moved by lr (1 + beta) g (any size)
-    a, b = off[0], off[1]
-    g = lut2[0][codes2[a:b].long()]
+    a, b = off[5], off[6]
+    g = lut2[5][codes2[a:b].long()]
     assert torch.equal(mom[a:b], g)
     say(f"[config2] stage 3 checked; total one-bucket flips on sampled tensors: {flips}")
 
@@ -517,15 +518,22 @@ def test_config3_fullsize_sampled_tensors(B, oracle_mod):
     th_s = {s: t2n(theta[off[s]:off[s + 1]]) for s in sample}
     o1 = {s: [] for s in sample}
     t0 = time.time()
+    flips1 = 0
     for p in range(W):
         synth.fill_theta_local(local, theta, p, "student_t3")
         B.pseudograd_quantize(theta, local, off, codes_out=peer_codes[p], lut_out=peer_luts[p], qparams_out=qp,
                               workspace=ws)
         torch.cuda.synchronize()
-        # the sampled tensors get the oracle's own stage-1 output (stage 2 is checked in isolation)
+        g_qp = B.qparams_to_numpy(qp)
+        assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
+        # stage 1 on heavy-tailed data at full size, checked on the sampled tensors; these then get the
+        # oracle's own stage-1 output (stage 2 is checked in isolation)
         for s in sample:
             a, b = off[s], off[s + 1]
             o = oracle_mod.pseudograd_quantize(th_s[s], t2n(local[a:b]), [0, b - a])
+            check_qparams(g_qp[s:s + 1], o[2])
+            flips1 += check_codes(t2n(peer_codes[p][a:b]), o[0], o[3], [0, b - a], o[2])
+            check_luts(t2n(peer_luts[p][s]), o[1], o[0], [0, b - a], o[2])
             o1[s].append(o)
             peer_codes[p][a:b].copy_(torch.from_numpy(o[0]))
             peer_luts[p][s].copy_(torch.from_numpy(o[1][0]))
@@ -538,6 +546,7 @@ def test_config3_fullsize_sampled_tensors(B, oracle_mod):
     g_qp = B.qparams_to_numpy(qp)
     assert int(g_qp["n"].sum()) == N and np.all(g_qp["status"] == 0)
     flips = 0
+    o2 = {}
     for s in sample:
         a, b = off[s], off[s + 1]
         o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[0] for o in o1[s]], [o[1] for o in o1[s]], [0, b - a], W)
@@ -545,12 +554,36 @@ def test_config3_fullsize_sampled_tensors(B, oracle_mod):
         flips += check_codes(t2n(codes2[a:b]), o_c2, o_acc, [0, b - a], o_q2)
         check_luts(t2n(lut2[s]), o_l2, o_c2, [0, b - a], o_q2)
         assert np.array_equal(t2n(local[a:b]), o_acc)                 # a fixed sequence of fp32 operations
+        o2[s] = (o_c2, o_l2)
     # any size: the requantised embedding tensor decodes to the same sum as the stored accumulation
     a, b = off[0], off[1]
     dec = lut2[0][codes2[a:b].long()].double()
     acc = local[a:b].double()
     assert abs(float(dec.sum() - acc.sum())) <= 2 ** -22 * float(acc.abs().sum())
-    say(f"[config3] stage 2 at W=14 checked on {len(sample)} tensors; one-bucket flips: {flips}")
+    say(f"[config3] stage 1 (x{W}) and stage 2 at W=14 checked on {len(sample)} tensors; one-bucket flips: "
+        f"{flips1} / {flips}")
+    # the outer step from the requantised average, over the full buffer (the coded contributions are
+    # consumed: their memory goes to the momentum buffer), checked on the sampled tensors from the
+    # oracle's own codes
+    del peer_codes, dec, acc
+    torch.cuda.empty_cache()
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        codes2[a:b].copy_(torch.from_numpy(o2[s][0]))
+        lut2[s].copy_(torch.from_numpy(o2[s][1][0]))
+    mom = torch.zeros(N, dtype=torch.float32, device=DEV)
+    handback = local.view(torch.bfloat16)[:N]                         # new worker weights over the consumed average
+    B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off,
+                 theta_local_out=handback, workspace=ws)
+    torch.cuda.synchronize()
+    for s in sample:
+        a, b = off[s], off[s + 1]
+        th_o, m_o = th_s[s].copy(), np.zeros(b - a, dtype=np.float32)
+        oracle_mod.outer_step(th_o, m_o, LR, BETA, delta_codes=o2[s][0], delta_luts=o2[s][1], seg_offsets=[0, b - a])
+        check_outer(t2n(mom[a:b]), m_o, np.zeros(b - a, dtype=np.float32), np.abs(m_o), "momentum")
+        check_outer(t2n(theta[a:b]), th_o, th_s[s], LR * (1 + BETA) * np.abs(m_o), "theta")
+    assert torch.equal(handback, theta.to(torch.bfloat16))           # any size: round to nearest even
+    say("[config3] outer step checked on the sampled tensors")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -558,40 +591,92 @@ def test_config3_fullsize_sampled_tensors(B, oracle_mod):
 # element offset of the full-size buffers), 13 coded contributions + the fp32 local addend
 # ---------------------------------------------------------------------------------------------
 
-def test_config4_fullsize_one_ring_chunk(B, oracle_mod):
+def test_config4_fullsize_ring_chunks(B, oracle_mod):
+    """Chunk 0 (starts at element 0), chunk 1 (odd offset) and chunk 13 (the short last one, 729,384,373
+    elements) of the full-size buffers, each reduced whole and compared with the oracle."""
     N = synth.n_elements(2)
     coff = synth.offsets_from_sizes(synth.ring_chunk_sizes(N, 14))
-    W, c = 13, 1
-    a, b = coff[c], coff[c + 1]
-    n = b - a
-    assert a % 2 == 1 and n == 729_384_375
+    W = 13
+    assert coff[1] % 2 == 1 and coff[2] - coff[1] == 729_384_375 and coff[14] - coff[13] == 729_384_373
     free, _ = torch.cuda.mem_get_info()
     if free < 190e9:
         pytest.skip(f"needs about 185 GB of free HBM, have {free / 1e9:.0f} GB")
-    say(f"[config4] chunk {c}: elements [{a}, {b}) of {N}, W={W} coded + fp32 local")
-    # full-size buffers, as the benchmark holds them; only this chunk's part is filled
+    # full-size buffers, as the benchmark holds them; only the chunk under test is filled
     local = torch.empty(N, dtype=torch.float32, device=DEV)
     peer_codes = [torch.empty(N, dtype=torch.uint8, device=DEV) for _ in range(W)]
     codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
     lut2 = torch.empty((14, 256), dtype=torch.float32, device=DEV)
-    synth.fill_delta(local[a:b], W, "mixture")
     peer_luts = [synth.synthetic_codebooks(14, p, device=DEV) for p in range(W)]
-    for p in range(W):
-        synth.fill_coded_contribution(peer_codes[p][a:b], p)
-    torch.cuda.synchronize()
-    h_local = t2n(local[a:b])
-    h_codes = [t2n(pc[a:b]) for pc in peer_codes]
-    h_luts = [t2n(pl[c:c + 1]) for pl in peer_luts]
-    codes_g, lut_g, qp_g = B.reduce_chunk([pc[a:b] for pc in peer_codes], [pl[c:c + 1] for pl in peer_luts], [0, n], 14,
-                                          local_fp32=local[a:b], acc_out=local[a:b], codes_out=codes2[a:b],
-                                          lut_out=lut2[c:c + 1])
+    for c in (0, 1, 13):
+        a, b = coff[c], coff[c + 1]
+        n = b - a
+        say(f"[config4] chunk {c}: elements [{a}, {b}) of {N}, W={W} coded + fp32 local")
+        synth.fill_delta(local[a:b], W, "mixture", seed=synth.BASE_SEED + c)
+        for p in range(W):
+            synth.fill_coded_contribution(peer_codes[p][a:b], p, seed=synth.BASE_SEED + c)
+        torch.cuda.synchronize()
+        h_local = t2n(local[a:b])
+        h_codes = [t2n(pc[a:b]) for pc in peer_codes]
+        h_luts = [t2n(pl[c:c + 1]) for pl in peer_luts]
+        codes_g, lut_g, qp_g = B.reduce_chunk([pc[a:b] for pc in peer_codes], [pl[c:c + 1] for pl in peer_luts],
+                                              [0, n], 14, local_fp32=local[a:b], acc_out=local[a:b],
+                                              codes_out=codes2[a:b], lut_out=lut2[c:c + 1])
+        torch.cuda.synchronize()
+        t0 = time.time()
+        o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce(h_codes, h_luts, [0, n], 14, local_fp32=h_local)
+        say(f"[config4] oracle reduce of chunk {c}: {time.time() - t0:.1f}s")
+        del h_codes
+        check_qparams(B.qparams_to_numpy(qp_g), o_q2, require_exact=1.0)
+        flips = check_codes(t2n(codes_g), o_c2, o_acc, [0, n], o_q2)
+        check_luts(t2n(lut_g), o_l2, o_c2, [0, n], o_q2)
+        assert np.array_equal(t2n(local[a:b]), o_acc)
+        say(f"[config4] chunk {c}: one-bucket flips: {flips} of {n}")
+        del o_acc, o_c2, h_local
+
+
+# ---------------------------------------------------------------------------------------------
+# one quantisation group per matrix row (Section 2.2 says "for each tensor"; the group is whatever the
+# caller declares): one decoder layer as 43,010 groups whose scales differ row by row, every element
+# and every group against the oracle, stage 1 and the reduce
+# ---------------------------------------------------------------------------------------------
+
+def test_per_row_groups_one_layer(B, oracle_mod):
+    row_sizes = synth.layer_row_sizes()
+    off = synth.offsets_from_sizes(row_sizes)
+    N, T = off[-1], len(row_sizes)
+    say(f"[rows] N={N} in {T} groups of 4,096 / 14,336 elements")
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local = synth.fill_theta_local(torch.empty(N, dtype=torch.float32, device=DEV), theta, 0, "mixture")
+    # rows with log-normally spread scales (sigma_ln = 1): theta_local = theta - scale_row * delta
+    g = torch.Generator(device=DEV).manual_seed(synth.BASE_SEED + 77)
+    scale = torch.exp(torch.randn(T, device=DEV, generator=g))
+    local = theta - (theta - local) * torch.repeat_interleave(scale, torch.tensor(row_sizes, device=DEV))
+    ws = B.new_workspace(T, DEV)
+    codes, luts, qp = B.pseudograd_quantize(theta, local, off, workspace=ws)
     torch.cuda.synchronize()
     t0 = time.time()
-    o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce(h_codes, h_luts, [0, n], 14, local_fp32=h_local)
-    say(f"[config4] oracle reduce of one chunk: {time.time() - t0:.1f}s")
-    del h_codes
-    check_qparams(B.qparams_to_numpy(qp_g), o_q2)
-    flips = check_codes(t2n(codes_g), o_c2, o_acc, [0, n], o_q2)
-    check_luts(t2n(lut_g), o_l2, o_c2, [0, n], o_q2)
-    assert np.array_equal(t2n(local[a:b]), o_acc)
-    say(f"[config4] one-bucket flips: {flips} of {n}")
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(t2n(theta), t2n(local), off)
+    say(f"[rows] oracle stage 1: {time.time() - t0:.1f}s")
+    exact = check_qparams(B.qparams_to_numpy(qp), o_qp)
+    flips = check_codes(t2n(codes), o_codes, o_d, off, o_qp)
+    worst = check_luts(t2n(luts), o_luts, o_codes, off, o_qp)
+    say(f"[rows] stage 1: {exact}/{T} groups with bit-equal range, flips={flips}, worst lut rel={worst:.2e}")
+    # the reduce of two such contributions (the second: the first one's codes reversed inside each row
+    # would need new codebooks, so simply the same contribution twice with divisor 2: the average decodes
+    # to the contribution itself) and of contribution + fp32 addend, both forms
+    pc, pl = torch.from_numpy(o_codes).to(DEV), torch.from_numpy(o_luts).to(DEV)
+    addend = torch.from_numpy(o_d).to(DEV).flip(0).contiguous()
+    h_addend = t2n(addend)
+    for form, kw_g, kw_o in (("W=2", dict(), dict()),
+                             ("W=1 + fp32 addend, in place", dict(local_fp32=addend, acc_out=addend),
+                              dict(local_fp32=h_addend))):
+        Wc = 2 if not kw_g else 1
+        c2, l2, q2 = B.reduce_chunk([pc] * Wc, [pl] * Wc, off, 2, workspace=ws, **kw_g)
+        torch.cuda.synchronize()
+        o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o_codes] * Wc, [o_luts] * Wc, off, 2, **kw_o)
+        exact = check_qparams(B.qparams_to_numpy(q2), o_q2)
+        flips = check_codes(t2n(c2), o_c2, o_acc, off, o_q2)
+        check_luts(t2n(l2), o_l2, o_c2, off, o_q2)
+        if kw_g:
+            assert np.array_equal(t2n(addend), o_acc)
+        say(f"[rows] reduce {form}: {exact}/{T} groups with bit-equal range, flips={flips}")

@@ -78,12 +78,12 @@ def test_random_shapes(oracle_mod, seed):
     # every other case with the staged, time-phased code writes that large buffers get by themselves
     phased = seed % 2 == 1
     if phased:
-        os.environ["DILOCO_WRITE_PHASE"] = ["40,10", "10,9", "100000,1"][seed // 2 % 3]
+        B.tune_write_phase(*[(40, 10), (10, 9), (100000, 1)][seed // 2 % 3])
     try:
         codes, luts, qp = B.pseudograd_quantize(th_t, l_t, off, codes_out=codes_buf[cs:cs + n])
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("DILOCO_WRITE_PHASE", None)
+        B.tune_write_phase(-1)
     o = [oracle_mod.pseudograd_quantize(th_np, bf16_bits(l) if bf16_local else l.numpy(), off, local_is_bf16=bf16_local)
          for l in locals_]
     check_qparams(B.qparams_to_numpy(qp), o[0][2])

@@ -134,12 +134,28 @@ def test_stage1_outlier_and_constant_segment(B, oracle_mod):
 
 
 def test_stage1_is_repeatable(B):
+    """Two calls on the same inputs.  The statistics are merged with fp64 atomic additions whose order
+    varies from launch to launch (blocks claim their chunks dynamically), so the mean and standard
+    deviation repeat only to a few units in the last place; once rounded to the fp32 pair the bucket index
+    uses they coincide except in the rare case that the fp64 value sits at a rounding boundary.  Given
+    equal (lo, 1 / width) everything else is exact: codes are pure fp32 arithmetic and the bucket sums
+    are integers, whose order of addition does not matter."""
     theta, locals_, off = synth.make_inputs(synth.ragged_sizes(1_000_000), 1, device=DEV)
-    c1, l1, _ = B.pseudograd_quantize(theta, locals_[0], off)
-    c2, l2, _ = B.pseudograd_quantize(theta, locals_[0], off)
+    c1, l1, q1 = B.pseudograd_quantize(theta, locals_[0], off)
+    c2, l2, q2 = B.pseudograd_quantize(theta, locals_[0], off)
     torch.cuda.synchronize()
-    assert torch.equal(c1, c2)                                      # codes never depend on atomics' order
-    assert torch.allclose(l1, l2, rtol=1e-6, atol=0)
+    q1, q2 = B.qparams_to_numpy(q1), B.qparams_to_numpy(q2)
+    sd = np.maximum(q1["std"], 1e-300)
+    assert np.all(np.abs(q1["mean"] - q2["mean"]) <= 1e-12 * sd) and np.all(np.abs(q1["std"] - q2["std"]) <= 1e-12 * sd)
+    same = (q1["lo"] == q2["lo"]) & (q1["inv_w"] == q2["inv_w"])
+    assert same.sum() >= len(same) - 1
+    c1, c2, l1, l2 = t2n(c1), t2n(c2), t2n(l1), t2n(l2)
+    for s in np.flatnonzero(same):
+        assert np.array_equal(c1[off[s]:off[s + 1]], c2[off[s]:off[s + 1]])
+        counts = np.bincount(c1[off[s]:off[s + 1]], minlength=256)
+        assert np.array_equal(l1[s][counts > 0], l2[s][counts > 0])
+    assert np.count_nonzero(c1 != c2) <= max(1, 1e-5 * c1.size)
+    assert np.allclose(l1, l2, rtol=1e-6, atol=0)
 
 
 def test_empty_input(B):
@@ -360,12 +376,16 @@ def test_chained_config0(B, oracle_mod):
 
     th_np = t2n(theta)
     o1 = [oracle_mod.pseudograd_quantize(th_np, t2n(l), off) for l in locals_]
+    flips1 = 0
     for p in range(W):
         check_qparams(B.qparams_to_numpy(g1[p][2]), o1[p][2])
-        check_codes(t2n(g1[p][0]), o1[p][0], o1[p][3], off, o1[p][2])
+        flips1 += check_codes(t2n(g1[p][0]), o1[p][0], o1[p][3], off, o1[p][2])
     o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce([o[0] for o in o1], [o[1] for o in o1], off, W)
     check_qparams(B.qparams_to_numpy(qp2), o_q2)
-    flips = check_codes(t2n(codes2), o_c2, o_acc, off, o_q2, budget=1e-5)   # upstream flips may add a few
+    # with no flip upstream the GPU's stage 2 saw the oracle's inputs bit for bit and the stage's own
+    # bar applies; a flipped upstream code changes that element's sum and can move the fp32 range by
+    # an ulp, which shifts about 1e-5 of the codes by one bucket
+    flips = check_codes(t2n(codes2), o_c2, o_acc, off, o_q2, budget=1e-6 if flips1 == 0 else 1e-5)
     th_o, m_o = th_np.copy(), np.zeros(n, dtype=np.float32)
     oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=off)
     g_dec = o_l2[0][o_c2]
@@ -375,7 +395,7 @@ def test_chained_config0(B, oracle_mod):
     scale = np.maximum(np.abs(th_o), 0.7 * 1.9 * np.abs(g_dec))
     assert np.all(diff[same] <= 1e-5 * scale[same])
     assert np.all(diff[~same] <= 0.7 * 1.9 * 1.01 * w2 + 1e-5 * scale[~same])   # a flipped code moves by one bucket
-    say(f"[chained] config0: stage-2 flips={flips}")
+    say(f"[chained] config0: stage-1 flips={flips1} stage-2 flips={flips}")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -516,15 +536,21 @@ def test_few_distinct_values_reconstruct(B, oracle_mod):
 
 # ---------------------------------------------------------------------------------------------
 # stage 1 with the codes held back for the write window (the path large buffers take), forced at
-# small sizes through the library's environment switch: ragged segments, heads and tails, a
+# small sizes through the library's instrumentation call: ragged segments, heads and tails, a
 # misaligned view, bf16, and windows so short or so long that either every flush is forced by a full
 # staging area or nearly every iteration falls inside a window
 # ---------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("timing", ["40,10", "100000,1", "10,9"])
+@pytest.fixture
+def builtin_write_phase_after(B):
+    yield
+    B.tune_write_phase(-1)
+
+
+@pytest.mark.parametrize("timing", [(40, 10), (100000, 1), (10, 9)])
 @pytest.mark.parametrize("local_dtype", [torch.float32, torch.bfloat16])
-def test_stage1_staged_code_writes(B, oracle_mod, monkeypatch, timing, local_dtype):
-    monkeypatch.setenv("DILOCO_WRITE_PHASE", timing)
+def test_stage1_staged_code_writes(B, oracle_mod, builtin_write_phase_after, timing, local_dtype):
+    B.tune_write_phase(*timing)
     sizes = synth.ragged_sizes(1_500_000) + [4096 * 9 + 5, 130, 4096 * 33]
     theta, locals_, off = synth.make_inputs(sizes, 1, device=DEV, local_dtype=local_dtype)
     _check_stage1(B, oracle_mod, theta, locals_[0], off, f"staged writes, timing {timing}")
@@ -536,7 +562,7 @@ def test_stage1_staged_code_writes(B, oracle_mod, monkeypatch, timing, local_dty
     th_buf[3:3 + n] = theta
     lo_buf[3:3 + n] = locals_[0]
     codes, luts, qp = B.pseudograd_quantize(th_buf[3:3 + n], lo_buf[3:3 + n], off, codes_out=co_buf[5:5 + n])
-    monkeypatch.setenv("DILOCO_WRITE_PHASE", "0")
+    B.tune_write_phase(0)
     ref = B.pseudograd_quantize(theta, locals_[0], off)
     torch.cuda.synchronize()
     assert torch.equal(codes, ref[0]) and torch.allclose(luts, ref[1], rtol=1e-6, atol=0)
