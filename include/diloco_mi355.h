@@ -62,6 +62,7 @@ extern "C" {
 #define DILOCO_MAX_PEERS 16u        /* largest W accepted by int8_reduce_chunk */
 #define DILOCO_MAX_SEGMENTS 65536u  /* largest T accepted */
 #define DILOCO_MAX_RING_NODES 20u   /* largest n accepted by diloco_ring_order */
+#define DILOCO_STATIC_MAX_SEGMENTS 512u /* largest T accepted by int8_reduce_chunk_static */
 
 #define DILOCO_OK 0
 #define DILOCO_ERR_NULL (-1)        /* a required pointer is NULL                         */
@@ -69,6 +70,7 @@ extern "C" {
 #define DILOCO_ERR_ALIGN (-3)       /* a pointer is not aligned to its element type        */
 #define DILOCO_ERR_WORKSPACE (-4)   /* workspace smaller than diloco_workspace_bytes(T)    */
 #define DILOCO_ERR_DTYPE (-5)       /* unknown dtype flag                                  */
+#define DILOCO_ERR_STATIC_LIMIT (-6) /* T above DILOCO_STATIC_MAX_SEGMENTS (int8_reduce_chunk_static) */
 
 #define DILOCO_CODEBOOK_MEAN 0u      /* codebook entry = average of the bucket's values (the paper's) */
 #define DILOCO_CODEBOOK_MIDPOINT 1u  /* codebook entry = centre of the bucket                         */
@@ -156,6 +158,28 @@ int32_t int8_reduce_chunk(const uint8_t* const* peer_codes, const float* const* 
                           const uint64_t* seg_offsets, uint32_t T, float* acc_out,
                           uint8_t* codes_out, float* lut_out, diloco_qparams* qparams_out,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * int8_reduce_chunk for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error behaviour as int8_reduce_chunk, without `workspace` and
+ * `workspace_bytes`: the scratch (segment offsets, fp64 sums, pivots, bucket bins, chunk counters) lives
+ * in a device array that is part of the library's code object, about 2.1 MB
+ * (= diloco_workspace_bytes(DILOCO_STATIC_MAX_SEGMENTS)), which every GPU the library runs on holds
+ * until the process ends.
+ *   - T > DILOCO_STATIC_MAX_SEGMENTS is refused with DILOCO_ERR_STATIC_LIMIT before anything is enqueued.
+ *   - The call allocates and frees nothing, on the host or on the device.  The first call on a device
+ *     looks up that device's address of the array (a symbol lookup, no allocation); make that first
+ *     call outside a stream capture.
+ *   - Every call on a GPU uses that GPU's one array (the call clears what must start at zero, on the
+ *     stream): calls on the same GPU must not overlap in time - order them on one stream, or with
+ *     events - or they race on the scratch.  Calls that pass their own workspace are unaffected.
+ */
+int32_t int8_reduce_chunk_static(const uint8_t* const* peer_codes, const float* const* peer_luts,
+                                 uint32_t W, const float* local_fp32, uint32_t divisor, uint64_t n,
+                                 const uint64_t* seg_offsets, uint32_t T, float* acc_out,
+                                 uint8_t* codes_out, float* lut_out, diloco_qparams* qparams_out,
+                                 void* stream);
 
 /*
  * The two quantising calls with the quantiser's two constants as arguments.  Section 2.2 fixes a

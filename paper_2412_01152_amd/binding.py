@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libdiloco_mi355.so")
 DTYPE_FP32 = 0
 DTYPE_BF16 = 1
 MAX_PEERS = 16
+STATIC_MAX_SEGMENTS = 512
 STATUS_DEGENERATE = 1
 STATUS_NONFINITE = 2
 STATUS_EMPTY = 4
@@ -31,7 +32,7 @@ assert QPARAMS_DTYPE.itemsize == QPARAMS_BYTES
 EXPORTS = ("diloco_workspace_bytes", "diloco_strerror", "diloco_pseudograd_quantize",
            "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes",
            "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant", "diloco_ring_order",
-           "diloco_tune_write_phase")
+           "diloco_tune_write_phase", "int8_reduce_chunk_static")
 
 CODEBOOK_MEAN, CODEBOOK_MIDPOINT = 0, 1
 
@@ -63,6 +64,8 @@ def load() -> ctypes.CDLL:
     lib.diloco_pseudograd_quantize.argtypes = [vp, vp, i32, u64, vp, u32, vp, vp, vp, vp, sz, vp]
     lib.int8_reduce_chunk.restype = i32
     lib.int8_reduce_chunk.argtypes = [vp, vp, u32, vp, u32, u64, vp, u32, vp, vp, vp, vp, vp, sz, vp]
+    lib.int8_reduce_chunk_static.restype = i32
+    lib.int8_reduce_chunk_static.argtypes = [vp, vp, u32, vp, u32, u64, vp, u32, vp, vp, vp, vp, vp]
     f64 = ctypes.c_double
     lib.diloco_pseudograd_quantize_variant.restype = i32
     lib.diloco_pseudograd_quantize_variant.argtypes = lib.diloco_pseudograd_quantize.argtypes + [f64, u32]
@@ -209,6 +212,28 @@ def reduce_chunk(peer_codes: List[torch.Tensor], peer_luts: List[torch.Tensor], 
     if rc != 0:
         raise DilocoError(rc, name)
     return codes_out, lut_out, qparams_out
+
+
+def reduce_chunk_static(peer_codes: List[torch.Tensor], peer_luts: List[torch.Tensor], seg_offsets, divisor: int,
+                        codes_out: torch.Tensor, lut_out: torch.Tensor, qparams_out: torch.Tensor,
+                        local_fp32: Optional[torch.Tensor] = None, acc_out: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    """int8_reduce_chunk_static: every output buffer comes from the caller, the scratch from the library's
+    static device array; nothing is allocated here or in the library."""
+    lib = load()
+    W = len(peer_codes)
+    assert len(peer_luts) == W
+    so, T = _seg_array(seg_offsets)
+    n = int(so[-1]) if so.size else 0
+    code_ptrs = (ctypes.c_void_p * max(W, 1))(*[c.data_ptr() for c in peer_codes])
+    lut_ptrs = (ctypes.c_void_p * max(W, 1))(*[l.data_ptr() for l in peer_luts])
+    rc = lib.int8_reduce_chunk_static(ctypes.cast(code_ptrs, ctypes.c_void_p), ctypes.cast(lut_ptrs, ctypes.c_void_p),
+                                      ctypes.c_uint32(W), _ptr(local_fp32), ctypes.c_uint32(divisor),
+                                      ctypes.c_uint64(n), ctypes.c_void_p(so.ctypes.data), ctypes.c_uint32(T),
+                                      _ptr(acc_out), _ptr(codes_out), _ptr(lut_out), _ptr(qparams_out),
+                                      _stream(stream))
+    if rc != 0:
+        raise DilocoError(rc, "int8_reduce_chunk_static")
 
 
 def outer_step(theta_outer: torch.Tensor, momentum: torch.Tensor, lr: float, beta: float,

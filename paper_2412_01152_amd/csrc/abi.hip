@@ -198,6 +198,34 @@ hipError_t reduce_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams
     }
 }
 
+// Scratch of the entry point that takes no workspace argument: one file-scope device array per GPU,
+// laid out like a caller's workspace for DILOCO_STATIC_MAX_SEGMENTS segments.  In host code the
+// array's name is only a handle; its device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = workspace_layout(DILOCO_STATIC_MAX_SEGMENTS).total;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];            // device address of `scratch` on device d, or nullptr
+
+// Device address of this device's copy of `scratch` (looked up at the first call on the device).
+int32_t static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int32_t)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int32_t)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int32_t)e;
+        if (!p) return (int32_t)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DILOCO_OK;
+}
+
 #define DILOCO_TRY(expr)                             \
     do {                                             \
         hipError_t e_ = (expr);                      \
@@ -356,6 +384,8 @@ const char* diloco_strerror(int32_t code) {
         case DILOCO_ERR_ALIGN: return "a pointer is not aligned to its element type";
         case DILOCO_ERR_WORKSPACE: return "workspace too small (see diloco_workspace_bytes)";
         case DILOCO_ERR_DTYPE: return "unknown dtype flag";
+        case DILOCO_ERR_STATIC_LIMIT:
+            return "more segments than the library's static scratch holds (DILOCO_STATIC_MAX_SEGMENTS)";
         default: break;
     }
     if (code > 0) return hipGetErrorString((hipError_t)code);
@@ -390,6 +420,18 @@ int32_t int8_reduce_chunk(const uint8_t* const* peer_codes, const float* const* 
     return reduce_chunk_impl(peer_codes, peer_luts, W, local_fp32, divisor, n, seg_offsets, T, acc_out, codes_out,
                              lut_out, qparams_out, workspace, workspace_bytes, (hipStream_t)stream,
                              kPaperQuantiser);
+}
+
+int32_t int8_reduce_chunk_static(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,
+                                 const float* local_fp32, uint32_t divisor, uint64_t n,
+                                 const uint64_t* seg_offsets, uint32_t T, float* acc_out, uint8_t* codes_out,
+                                 float* lut_out, diloco_qparams* qparams_out, void* stream) {
+    if (T > DILOCO_STATIC_MAX_SEGMENTS) return DILOCO_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    int32_t rc = static_scratch(&ws);
+    if (rc) return rc;
+    return reduce_chunk_impl(peer_codes, peer_luts, W, local_fp32, divisor, n, seg_offsets, T, acc_out, codes_out,
+                             lut_out, qparams_out, ws, kStaticScratchBytes, (hipStream_t)stream, kPaperQuantiser);
 }
 
 int32_t int8_reduce_chunk_variant(const uint8_t* const* peer_codes, const float* const* peer_luts, uint32_t W,

@@ -86,6 +86,12 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert r(vp(0), pp, 2, vp(0), 2, 16, sp, 1, vp(0), fake, fake, fake, fake, 1 << 20, vp(0)) == -1
     assert r(pp, pp, 2, vp(0), 2, 16, sp, 1, vp(0), fake, fake, fake, fake, 16, vp(0)) == -4
 
+    # the entry point with the library's own static scratch: the segment limit is checked first
+    rs = lib.int8_reduce_chunk_static
+    big = _seg(list(range(0, 514)))
+    assert rs(pp, pp, 2, vp(0), 2, 513, vp(big.ctypes.data), 513, vp(0), fake, fake, fake, vp(0)) == -6
+    assert len(lib.diloco_strerror(-6)) > 3
+
     qv, rv = lib.diloco_pseudograd_quantize_variant, lib.int8_reduce_chunk_variant
     args_q = (fake, fake, 0, 16, sp, 1, fake, fake, fake, fake, 1 << 20, vp(0))
     args_r = (pp, pp, 2, vp(0), 2, 16, sp, 1, vp(0), fake, fake, fake, fake, 1 << 20, vp(0))
