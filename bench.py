@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="after the timed steps also time the other variants of the three calls on the same "
                          "resident data (bf16 theta_local, stored accumulation, fp32 delta, hand-back)")
+    ap.add_argument("--no-also", action="store_true",
+                    help="config 2: only the graded step, without the other full-size shapes that the default run "
+                         "appends under \"also\" (profiling runs)")
     ap.add_argument("--aligned-chunks", action="store_true",
                     help="config 4 only: round the ring chunk up to a multiple of 1024 elements")
     ap.add_argument("--overlap", action="store_true",
@@ -111,6 +114,122 @@ def main():
         return bench_config3(args, np, torch, B, synth, dev)
     if cfg == 4:
         return (bench_config4_overlap if args.overlap else bench_config4)(args, np, torch, B, synth, dev)
+    # The graded line is configuration 2's step.  The default run then re-uses the same arena for the other
+    # full-size shapes of the target table (the reduce at W = 14, the 14 ring-chunk calls with the outer step
+    # behind them, stage 1 with a bf16 theta_local, one GPU's eighth of every tensor) and appends them to the
+    # same JSON line under "also"; none of that is inside the timed region of the step.
+    also_wanted = cfg == 2 and args.shard == 1 and not args.no_also
+    result, arena = run_step_benchmark(args, np, torch, B, synth, dev, cfg, want_extras=args.extras or also_wanted)
+    fracs = {k: v["frac_of_peak"] for k, v in result["kernels"].items()}
+    if also_wanted:
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        result["also"] = measure_also(args, np, torch, B, synth, dev, arena)
+        for name in ("config3_reduce_w14", "config4_ring_chunks"):
+            for k, v in (result["also"].get(name) or {}).get("kernels", {}).items():
+                fracs[f"{name}: {k}"] = v["frac_of_peak"]
+    worst = min(fracs, key=fracs.get)
+    result["min_kernel_frac_of_peak"] = {"kernel": worst, "frac": fracs[worst]}
+    print(json.dumps(result), flush=True)
+
+
+def measure_also(args, np, torch, B, synth, dev, arena):
+    """The other full-size shapes, one after the other in the memory the step benchmark used."""
+    def fresh_alloc():
+        if arena is None:
+            return lambda numel, dtype: torch.empty(numel, dtype=dtype, device=dev)
+        arena.pos = 0
+
+        def carve(numel, dtype):
+            try:
+                return arena.carve(numel, dtype)
+            except RuntimeError:
+                return torch.empty(numel, dtype=dtype, device=dev)
+        return carve
+
+    import gc
+    also = {}
+    steps = max(3, args.steps // 2)
+    for name, fn in (("config3_reduce_w14", measure_config3), ("config4_ring_chunks", measure_config4)):
+        try:
+            r = fn(args, np, torch, B, synth, dev, fresh_alloc(), steps, 1)
+            also[name] = {k: r[k] for k in ("value", "unit", "ms_per_step", "frac_of_hbm_peak", "steps", "kernels",
+                                             "outer_step_after", "stage1_bf16_theta_local", "roofline") if k in r}
+            also[name]["workload"] = r["config"]["workload"]
+            also[name]["bytes_per_element"] = r["config"]["bytes_per_element_per_step"]
+        except RuntimeError as e:                 # not enough free HBM (another process on the card)
+            log(f"[bench] {name} skipped: {e}")
+            also[name] = None
+        gc.collect()
+        torch.cuda.empty_cache()
+    shard = {"buffers spread over the arena by role": measure_shard(args, np, torch, B, synth, dev, arena, 8, True)}
+    if arena is not None:                         # hand the memory back: the next measurement allocates per buffer
+        arena.buf = None
+        arena.nbytes = 0
+    gc.collect()
+    torch.cuda.empty_cache()
+    shard["one allocation per buffer"] = measure_shard(args, np, torch, B, synth, dev, None, 8, False)
+    also["config2_shard_1_of_8"] = shard
+    return also
+
+
+def measure_shard(args, np, torch, B, synth, dev, arena, K, spread):
+    """One GPU's share under the paper's hybrid scheme (Section 2.3): a K-th of every tensor of configuration 2,
+    the same 381 quantisation groups; the three calls of the step, per call."""
+    from paper_2412_01152_amd.arena import role_bases
+    sizes = [-(-s // K) for s in synth.config_segment_sizes(2)]
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 4
+    bases = role_bases(arena) if (spread and arena is not None and arena.nbytes >= (210 << 30)) else None
+    if spread and bases is None:
+        return None
+
+    def alloc(numel, dtype, at=None):
+        if bases is not None:
+            return arena.carve(numel, dtype, at=at)
+        return torch.empty(numel, dtype=dtype, device=dev)
+
+    theta = alloc(N, torch.float32, at=bases["read"] if bases else None)
+    local = alloc(N, torch.float32)
+    peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
+    mom = alloc(N, torch.float32, at=bases["state"] if bases else None).zero_()
+    codes1 = alloc(N, torch.uint8)
+    codes2 = alloc(N, torch.uint8, at=bases["out"] if bases else None)
+    peer_luts = [torch.empty((T, 256), dtype=torch.float32, device=dev) for _ in range(W)]
+    lut1 = torch.empty((T, 256), dtype=torch.float32, device=dev)
+    lut2 = torch.empty((T, 256), dtype=torch.float32, device=dev)
+    qp, ws = B.new_qparams(T, dev), B.new_workspace(T, dev)
+    synth.fill_theta_outer(theta)
+    for p in list(range(1, W)) + [0]:
+        synth.fill_theta_local(local, theta, p, "mixture")
+        B.pseudograd_quantize(theta, local, off, codes_out=peer_codes[p], lut_out=peer_luts[p], qparams_out=qp,
+                              workspace=ws)
+    calls = (("stage1", 17, lambda: B.pseudograd_quantize(theta, local, off, codes_out=codes1, lut_out=lut1,
+                                                          qparams_out=qp, workspace=ws)),
+             ("stage2", 2 * W + 1, lambda: B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2,
+                                                          qparams_out=qp, workspace=ws)),
+             ("stage3", 17, lambda: B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2,
+                                                 seg_offsets=off, workspace=ws)))
+    out = {"elements": N}
+    reps = 10
+    for name, bpe, fn in calls:
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = call_record(e0.elapsed_time(e1) / reps, bpe, N)
+    log(f"[bench] shard 1/{K} ({'spread' if bases else 'plain allocations'}): "
+        + "  ".join(f"{k} {out[k]['ms']:.3f} ms {100 * out[k]['frac_of_peak']:.1f}%" for k in ("stage1", "stage2", "stage3")))
+    return out
+
+
+def run_step_benchmark(args, np, torch, B, synth, dev, cfg, want_extras):
+    """One step = the three calls on one configuration's buffers; returns (result record, the arena or None)."""
     sizes = synth.config_segment_sizes(cfg)
     sharded = cfg == 2 and args.shard > 1
     if sharded:
@@ -178,7 +297,7 @@ def main():
     # to theta like the fp32 one (reads run fastest from the same part of the memory), and the room in
     # front of theta is free when the state was shifted far enough
     bf16_slot = None
-    if arena is not None and not spread and args.extras and shift >= 2 * N + 8192:
+    if arena is not None and not spread and want_extras and shift >= 2 * N + 8192:
         bf16_slot = arena.buf[shift - 2 * N - 4096:shift - 4096].view(torch.bfloat16)
     theta = alloc(N, torch.float32, at=shift if arena is not None else None)
     local = alloc(N, torch.float32)
@@ -297,7 +416,7 @@ def main():
         med = float(np.median(v))
         stages[s] = {"avg_ms": round(avg, 4), "median_ms": round(med, 4), "min_ms": round(float(np.min(v)), 4),
                      "GB/s": round(STAGE_BYTES[s] * N / (avg * 1e-3) / 1e9, 1),
-                     "frac_of_peak": round(STAGE_BYTES[s] * N / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                     "frac_of_peak": round(STAGE_BYTES[s] * N / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         log(f"[bench] {s}: {avg:.3f} ms  {stages[s]['GB/s']:.1f} GB/s ({100 * stages[s]['GB/s'] / HBM_PEAK_GBS:.1f}%)")
     graph = None
     if args.graph:
@@ -341,12 +460,12 @@ def main():
             f"bytes, {100 * ceiling['GB/s'] / HBM_PEAK_GBS:.1f}% of the HBM peak)")
         B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
     extras = None
-    if args.extras:
+    if want_extras:
         extras = time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1, codes2, lut2, qp, ws,
                              off, N, T, W, alloc, bf16_slot)
     dominant = max(names, key=lambda n: kernels[n]["avg_ms"])
     achieved = kernels[dominant]["GB/s"]
-    traffic = measured_traffic_bytes(dominant) if cfg == 2 and not sharded else None
+    traffic = measured_traffic_bytes("hbm_traffic_config2.txt", dominant) if cfg == 2 and not sharded else None
     result = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
@@ -364,7 +483,7 @@ def main():
         "kernels": kernels, "stages": stages, "extras": extras, "graph": graph, "stage2_compute_ceiling": ceiling,
         "cpu_baseline": cpu_baseline,
     }
-    print(json.dumps(result), flush=True)
+    return result, arena
 
 
 def study_ring(args, np, torch, B, synth, dev):
@@ -523,16 +642,15 @@ def arena_alloc(args, torch, dev):
     return carve
 
 
-def bench_config3(args, np, torch, B, synth, dev):
+def measure_config3(args, np, torch, B, synth, dev, alloc, steps, warmup):
     """Configuration 3: the reduce step alone at W = 14 heavy-tailed coded peers on the full 10B set
     (143 GB of codes resident), accumulation stored over theta_local (no room for a fourth fp32 array
-    next to theta_outer, theta_local and momentum in the real layout)."""
+    next to theta_outer, theta_local and momentum in the real layout).  Returns the result record."""
     sizes = synth.config_segment_sizes(3)
     off = synth.offsets_from_sizes(sizes)
     N, T, W = off[-1], len(sizes), 14
     log(f"[bench] config 3: N={N} T={T} W={W}; allocating {(W + 1) * N / 1e9 + 8 * N / 1e9:.0f} GB")
     t0 = time.time()
-    alloc = arena_alloc(args, torch, dev)
     theta = alloc(N, torch.float32)
     local = alloc(N, torch.float32)
     peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
@@ -555,18 +673,18 @@ def bench_config3(args, np, torch, B, synth, dev):
         B.reduce_chunk(peer_codes, peer_luts, off, W, acc_out=local, codes_out=codes2, lut_out=lut2,
                        qparams_out=qp, workspace=ws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     evs = []
-    for _ in range(args.steps):
+    for _ in range(steps):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         for x in e:
             x.record()
         evs.append(e)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         step([x.cuda_event for x in evs[k]])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
@@ -574,31 +692,38 @@ def bench_config3(args, np, torch, B, synth, dev):
     a_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     b_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
     bpe = W + 9
-    value = bpe * N / (elapsed / args.steps) / 1e9
-    kernels = {f"stage2_stats(reduce W={W}, store acc)": {"avg_ms": round(a_ms, 3), "GB/s": round((W + 4) * N / a_ms / 1e6, 1)},
-               "stage2_quant(stored acc)": {"avg_ms": round(b_ms, 3), "GB/s": round(5 * N / b_ms / 1e6, 1)}}
+    value = bpe * N / (elapsed / steps) / 1e9
+    kernels = {f"stage2_stats(reduce W={W}, store acc)": kernel_record(a_ms, (W + 4) * N),
+               "stage2_quant(stored acc)": kernel_record(b_ms, 5 * N)}
     for k, v in kernels.items():
-        log(f"[bench] {k:40s} avg {v['avg_ms']:8.3f} ms  {v['GB/s']:8.1f} GB/s  {100 * v['GB/s'] / HBM_PEAK_GBS:.1f}% of peak")
+        log(f"[bench] {k:40s} avg {v['avg_ms']:8.3f} ms  {v['GB/s']:8.1f} GB/s  {100 * v['frac_of_peak']:.1f}% of peak")
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
-    result = {"metric": "int8 reduce W=14 (stored accumulation): GB/s & % HBM peak, 10B", "value": round(value, 1),
-              "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-              "ms_per_step": round(elapsed * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
-              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-              "config": {"workload": f"config3: 10B-shaped parameter set, {N} elements in {T} tensors, W=14 coded "
-                                     f"peers (Student-t nu=3 deltas), int8_reduce_chunk only", "elements": N,
-                         "segments": T, "peers": W, "bytes_per_element_per_step": bpe},
-              "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-              "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GB/s"], "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": round(kernels[dom]["GB/s"] / HBM_PEAK_GBS, 4), "traffic": None},
-              "kernels": kernels, "cpu_baseline": None}
+    return {"metric": "int8 reduce W=14 (stored accumulation): GB/s & % HBM peak, 10B", "value": round(value, 1),
+            "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": round(elapsed * 1e3 / steps, 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"config3: 10B-shaped parameter set, {N} elements in {T} tensors, W=14 coded "
+                                   f"peers (Student-t nu=3 deltas), int8_reduce_chunk only", "elements": N,
+                       "segments": T, "peers": W, "bytes_per_element_per_step": bpe},
+            "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+            "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GB/s"], "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": round(kernels[dom]["GB/s"] / HBM_PEAK_GBS, 4),
+                         "traffic": measured_traffic_bytes("hbm_traffic_config3_config4.txt", dom),
+                         "algorithmic_bytes_per_launch": (W + 4) * N if dom.startswith("stage2_stats") else 5 * N},
+            "kernels": kernels, "cpu_baseline": None}
+
+
+def bench_config3(args, np, torch, B, synth, dev):
+    result = measure_config3(args, np, torch, B, synth, dev, arena_alloc(args, torch, dev), args.steps, args.warmup)
     print(json.dumps(result), flush=True)
 
 
-def bench_config4(args, np, torch, B, synth, dev):
+def measure_config4(args, np, torch, B, synth, dev, alloc, steps, warmup):
     """Configuration 4: ring granularity.  The 10B set is cut into 14 contiguous chunks of
     ceil(N / 14) = 729,384,375 elements (odd: every other chunk starts on a 4-byte boundary only);
     int8_reduce_chunk runs once per chunk on 13 coded contributions plus the owner's fp32 data
-    (stored in place), each chunk its own quantisation group.  One step = the 14 calls."""
+    (stored in place), each chunk its own quantisation group.  One step = the 14 calls; then the outer
+    step from the 14 requantised chunks, and stage 1 with a bf16 theta_local on the same 14 groups."""
     N = synth.n_elements(2)
     chunk_sizes = synth.ring_chunk_sizes(N, 14)
     if args.aligned_chunks:                       # chunk rounded up to a multiple of 1024 elements
@@ -608,7 +733,6 @@ def bench_config4(args, np, torch, B, synth, dev):
     W = 13
     log(f"[bench] config 4: N={N}, 14 chunks of {chunk_sizes[0]} (last {chunk_sizes[-1]}), W={W} coded + local")
     t0 = time.time()
-    alloc = arena_alloc(args, torch, dev)
     theta = alloc(N, torch.float32)
     local = alloc(N, torch.float32)
     peer_codes = [alloc(N, torch.uint8) for _ in range(W)]
@@ -628,24 +752,44 @@ def bench_config4(args, np, torch, B, synth, dev):
     log(f"[bench] {W} peers ready ({time.time() - t0:.1f}s)")
     qp1 = B.new_qparams(1, dev)
 
-    def step():
+    def step(events=None):
         for c in range(14):
             a, b = coff[c], coff[c + 1]
+            if events is not None:
+                B.profile_passes(events[c])
             B.reduce_chunk([pc[a:b] for pc in peer_codes], [pl[c:c + 1] for pl in peer_luts], [0, b - a], 14,
                            local_fp32=local[a:b], acc_out=local[a:b], codes_out=codes2[a:b],
                            lut_out=lut2[c:c + 1], qparams_out=qp1, workspace=ws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     bpe = W + 13
-    value = bpe * N / (elapsed / args.steps) / 1e9
-    log(f"[bench] 14 chunk calls: {elapsed * 1e3 / args.steps:.3f} ms  {value:.1f} GB/s ({100 * value / HBM_PEAK_GBS:.1f}% of peak)")
+    value = bpe * N / (elapsed / steps) / 1e9
+    log(f"[bench] 14 chunk calls: {elapsed * 1e3 / steps:.3f} ms  {value:.1f} GB/s ({100 * value / HBM_PEAK_GBS:.1f}% of peak)")
+    # one more step with the library's events around the two passes of every call: per-kernel durations
+    evs = []
+    for _ in range(14):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for x in e:
+            x.record()
+        evs.append(e)
+    torch.cuda.synchronize()
+    step([[x.cuda_event for x in e] for e in evs])
+    torch.cuda.synchronize()
+    B.profile_passes(None)
+    a_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs[:13]]))       # the 13 full-length chunks
+    b_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs[:13]]))
+    n0 = chunk_sizes[0]
+    kernels = {f"stage2_stats(reduce W={W} + fp32 local, store acc in place), one chunk": kernel_record(a_ms, (W + 8) * n0),
+               "stage2_quant(stored acc), one chunk": kernel_record(b_ms, 5 * n0)}
+    for k, v in kernels.items():
+        log(f"[bench] {k:40s} avg {v['avg_ms']:8.3f} ms  {v['GB/s']:8.1f} GB/s  {100 * v['frac_of_peak']:.1f}% of peak")
     # then the outer step from the requantised chunks (14 quantisation groups at the odd chunk offsets)
     outer = None
     try:
@@ -656,25 +800,46 @@ def bench_config4(args, np, torch, B, synth, dev):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=coff, workspace=ws)
         e0.record()
-        for _ in range(max(1, args.steps)):
+        for _ in range(max(1, steps)):
             B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=coff, workspace=ws)
         e1.record()
         torch.cuda.synchronize()
-        o_ms = e0.elapsed_time(e1) / max(1, args.steps)
-        o_gbs = 17 * N / (o_ms * 1e-3) / 1e9
-        outer = {"ms": round(o_ms, 3), "bytes_per_element": 17, "GB/s": round(o_gbs, 1),
-                 "frac_of_peak": round(o_gbs / HBM_PEAK_GBS, 4)}
-        log(f"[bench] then the outer step from the 14 requantised chunks: {o_ms:.3f} ms  {o_gbs:.1f} GB/s "
-            f"({100 * o_gbs / HBM_PEAK_GBS:.1f}% of peak)")
-    result = {"metric": "int8 reduce per ring chunk, 13 coded + fp32 local: GB/s & % HBM peak, 10B",
-              "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-              "ms_per_step": round(elapsed * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
-              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-              "config": {"workload": f"config4: {N} elements as 14 ring chunks of {chunk_sizes[0]}, 13 coded peers + "
-                                     f"fp32 local, divisor 14, one int8_reduce_chunk call per chunk",
-                         "elements": N, "segments": 14, "peers": W, "bytes_per_element_per_step": bpe},
-              "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "outer_step_after": outer, "roofline": None,
-              "cpu_baseline": None}
+        outer = call_record(e0.elapsed_time(e1) / max(1, steps), 17, N)
+        log(f"[bench] then the outer step from the 14 requantised chunks: {outer['ms']:.3f} ms  {outer['GB/s']:.1f} GB/s "
+            f"({100 * outer['frac_of_peak']:.1f}% of peak)")
+    # stage 1 of this configuration: bf16 theta_local, one quantisation group per ring chunk; the bf16 copy is
+    # written over the first half of the consumed fp32 accumulation (right behind theta)
+    local16 = local.view(torch.bfloat16)[:N]
+    synth.fill_theta_local(local16, theta, 0, "mixture")
+    B.pseudograd_quantize(theta, local16, coff, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(max(1, steps)):
+        B.pseudograd_quantize(theta, local16, coff, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    stage1_bf16 = call_record(e0.elapsed_time(e1) / max(1, steps), 13, N)
+    log(f"[bench] stage 1 with bf16 theta_local, 14 groups: {stage1_bf16['ms']:.3f} ms  {stage1_bf16['GB/s']:.1f} GB/s "
+        f"({100 * stage1_bf16['frac_of_peak']:.1f}% of peak)")
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    return {"metric": "int8 reduce per ring chunk, 13 coded + fp32 local: GB/s & % HBM peak, 10B",
+            "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": round(elapsed * 1e3 / steps, 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"config4: {N} elements as 14 ring chunks of {chunk_sizes[0]}, 13 coded peers + "
+                                   f"fp32 local, divisor 14, one int8_reduce_chunk call per chunk",
+                       "elements": N, "segments": 14, "peers": W, "bytes_per_element_per_step": bpe},
+            "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "kernels": kernels, "outer_step_after": outer,
+            "stage1_bf16_theta_local": stage1_bf16,
+            "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["GB/s"], "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": round(kernels[dom]["GB/s"] / HBM_PEAK_GBS, 4),
+                         "traffic": measured_traffic_bytes("hbm_traffic_config3_config4.txt", dom),
+                         "algorithmic_bytes_per_launch": (W + 8) * n0 if dom.startswith("stage2_stats") else 5 * n0},
+            "cpu_baseline": None}
+
+
+def bench_config4(args, np, torch, B, synth, dev):
+    result = measure_config4(args, np, torch, B, synth, dev, arena_alloc(args, torch, dev), args.steps, args.warmup)
     print(json.dumps(result), flush=True)
 
 
@@ -823,22 +988,56 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
     return out
 
 
-def measured_traffic_bytes(kernel_name):
-    """HBM bytes per launch of `kernel_name` from the committed rocprofv3 counter summary
-    (profiles/hbm_traffic_config2.txt: FETCH_SIZE and WRITE_SIZE in KiB per dispatch and the factors
-    that a plain copy of known size gave for the same counters).  None if the file or the row is
-    missing: the figure is measured offline, never estimated here."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_config2.txt")
+def kernel_record(avg_ms, bytes_per_launch):
+    gbs = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    return {"avg_ms": round(avg_ms, 4), "GB/s": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def call_record(ms, bytes_per_elem, n):
+    gbs = bytes_per_elem * n / (ms * 1e-3) / 1e9
+    return {"ms": round(ms, 3), "bytes_per_element": bytes_per_elem, "GB/s": round(gbs, 1),
+            "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def csrc_sha16():
+    """Hash of the library's sources: the counter summaries under profiles/ carry the hash of the sources they
+    were measured with, and a summary taken with other sources is not quoted."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2412_01152_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".h", ".hip", ".cpp", ".c")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic_bytes(profile_file, kernel_name):
+    """HBM bytes per launch of `kernel_name` from a committed rocprofv3 counter summary under profiles/
+    (FETCH_SIZE and WRITE_SIZE in KiB per dispatch and the factors that a plain copy of known size gave for
+    the same counters).  The figure is measured offline, never estimated here: None if the file or the row is
+    missing, or if the file was taken with other kernel sources than the ones in the tree (its csrc_sha16
+    line differs from the hash of csrc/ now)."""
+    path = os.path.join(ROOT, "profiles", profile_file)
     if not os.path.exists(path):
         return None
+    stamp_ok = False
+    row = None
     for line in open(path):
+        if line.startswith("# csrc_sha16:"):
+            stamp_ok = line.split(":", 1)[1].strip() == csrc_sha16()
         if line.startswith("#") or "|" not in line:
             continue
         cols = [c.strip() for c in line.split("|")]
         if cols[0] == kernel_name and len(cols) >= 5:
             fetch_kib, write_kib, fetch_factor, write_factor = (float(c) for c in cols[1:5])
-            return round((fetch_kib / fetch_factor + write_kib / write_factor) * 1024.0)
-    return None
+            row = round((fetch_kib / fetch_factor + write_kib / write_factor) * 1024.0)
+    if not stamp_ok:
+        if row is not None:
+            log(f"[bench] profiles/{profile_file} was taken with other kernel sources: traffic not quoted")
+        return None
+    return row
 
 
 def host_cpu_model():
