@@ -928,6 +928,44 @@ def bench_config4_overlap(args, np, torch, B, synth, dev):
         f"{(t_overlap - t_copy) * 1e3:.2f} ms of {t_reduce * 1e3:.2f})")
     log(f"[bench] one reduce call, median of 13: alone {ms_alone[6]:.3f} ms, beside a transfer {ms_under[6]:.3f} ms "
         f"(+{100 * (ms_under[6] / ms_alone[6] - 1):.1f}%)")
+    # The same pipeline with the contributions arriving from device memory: a second resident copy of one
+    # chunk's coded contributions is copied into the staging set on the copy stream (device-to-device, at
+    # hundreds of GB/s instead of the host link's tens) while the previous chunk is reduced; 1, 4 or all 13
+    # of a chunk's contributions arrive that way, the others are already in place.
+    dev_codes = [torch.empty(n0, dtype=torch.uint8, device=dev).copy_(h, non_blocking=True) for h in host_codes]
+    dev_luts = [h.to(dev) for h in host_luts]
+    torch.cuda.synchronize()
+    d2d = {}
+    for inbound in (1, 4, W):
+        def arrive_d2d(c, code_bufs, lut_bufs, k=inbound):
+            n = coff[c + 1] - coff[c]
+            for p in range(k):
+                code_bufs[p].copy_(dev_codes[p][:n], non_blocking=True)
+                lut_bufs[p].copy_(dev_luts[p], non_blocking=True)
+
+        def copy_only_d2d():
+            with torch.cuda.stream(copy_stream):
+                for c in range(14):
+                    ph, n = coff[c] % 128, coff[c + 1] - coff[c]
+                    arrive_d2d(c, [b[ph:ph + n] for b in staging[0][c & 1]], staging[1][c & 1])
+            torch.cuda.current_stream().wait_stream(copy_stream)
+
+        t_c = timed(copy_only_d2d, 2)
+        t_o = timed(lambda: run(arrive_d2d, True), 2)
+        ev_a, ev_u = [], []
+        run(arrive_d2d, False, ev_a)
+        run(arrive_d2d, True, ev_u)
+        torch.cuda.synchronize()
+        m_a = sorted(a.elapsed_time(b) for a, b in ev_a[:13])
+        m_u = sorted(a.elapsed_time(b) for a, b in ev_u[:13])
+        rate = inbound * N / t_c / 1e9
+        d2d[f"{inbound} of {W} contributions inbound"] = {
+            "transfer_alone_ms": round(t_c * 1e3, 2), "inbound_GB/s": round(rate, 1),
+            "pipelined_ms": round(t_o * 1e3, 2),
+            "reduce_call_ms": {"alone": round(m_a[6], 3), "beside_transfer": round(m_u[6], 3)}}
+        log(f"[bench] device-to-device arrival, {inbound:2d} of {W} contributions: transfer alone {t_c * 1e3:7.2f} ms "
+            f"({rate:.0f} GB/s inbound), pipelined {t_o * 1e3:7.2f} ms (14 reduces alone {t_reduce * 1e3:.2f}); one reduce "
+            f"call {m_a[6]:.3f} ms alone, {m_u[6]:.3f} ms beside the transfer (+{100 * (m_u[6] / m_a[6] - 1):.1f}%)")
     result = {"metric": "ring-chunk pipeline: transfer of chunk c+1 overlapping int8 reduce of chunk c, 10B",
               "value": round(t_overlap * 1e3, 2), "unit": "ms", "n_gpus": 1, "steps": 1, "warmup": 1,
               "ms_per_step": round(t_overlap * 1e3, 2), "higher_is_better": False, "scaling": "weak",
@@ -937,7 +975,8 @@ def bench_config4_overlap(args, np, torch, B, synth, dev):
               "transfer_alone_ms": round(t_copy * 1e3, 2), "reduce_alone_ms": round(t_reduce * 1e3, 2),
               "serial_ms": round(t_serial * 1e3, 2), "pipelined_ms": round(t_overlap * 1e3, 2),
               "h2d_GB/s": round(h2d, 1),
-              "reduce_call_ms": {"alone": round(ms_alone[6], 3), "beside_transfer": round(ms_under[6], 3)}, "roofline": None, "cpu_baseline": None}
+              "reduce_call_ms": {"alone": round(ms_alone[6], 3), "beside_transfer": round(ms_under[6], 3)},
+              "device_to_device_arrival": d2d, "roofline": None, "cpu_baseline": None}
     print(json.dumps(result), flush=True)
 
 

@@ -25,24 +25,79 @@ PassEvents& pass_events() {
 namespace {
 
 // Segment offsets travel to the device inside kernel arguments (no staging copy, no host
-// synchronisation): 256 offsets per launch of a one-block kernel.
+// synchronisation, nothing but kernels on the stream).  A launch's arguments may take 4 KiB: up to
+// 480 offsets go up as they are, in one launch.  Longer tables go up as 32-bit segment lengths,
+// 960 per launch, and one more kernel turns them into offsets with a prefix sum (66 + 1 launches at
+// the largest table the library takes); a table with a segment of 2^32 elements or more falls back
+// to 64-bit offsets, 480 per launch.
+constexpr uint32_t kOffsetsPerLaunch = 480;
+constexpr uint32_t kLengthsPerLaunch = 960;
 struct OffsetBlock {
-    uint64_t v[256];
+    uint64_t v[kOffsetsPerLaunch];
 };
-__global__ void upload_offsets_kernel(OffsetBlock blk, uint64_t* dst, uint32_t count) {
-    if (threadIdx.x < count) dst[threadIdx.x] = blk.v[threadIdx.x];
+struct LengthBlock {
+    uint32_t v[kLengthsPerLaunch];
+};
+template <class Block>
+__global__ void upload_block_kernel(Block blk, uint64_t* dst, uint32_t count) {
+    for (uint32_t i = threadIdx.x; i < count; i += blockDim.x) dst[i] = blk.v[i];
+}
+
+// In-place inclusive prefix sum of v[0 .. count) by one block of 1,024 threads: every thread sums
+// a contiguous slice, the 1,024 slice sums are scanned with wave shuffles, every thread rewrites
+// its slice.
+__global__ __launch_bounds__(1024) void scan_offsets_kernel(uint64_t* v, uint32_t count) {
+    __shared__ uint64_t s_wave[16];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t per = (count + 1023) / 1024;
+    const uint32_t a = tid * per < count ? tid * per : count;
+    const uint32_t b = a + per < count ? a + per : count;
+    uint64_t sum = 0;
+    for (uint32_t i = a; i < b; ++i) sum += v[i];
+    uint64_t incl = sum;                                  // inclusive scan of the slice sums within the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint64_t up = __shfl_up(incl, o, 64);
+        if (lane >= (uint32_t)o) incl += up;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    uint64_t before = incl - sum;                         // everything in front of this thread's slice
+    for (uint32_t w = 0; w < wave; ++w) before += s_wave[w];
+    for (uint32_t i = a; i < b; ++i) {
+        before += v[i];
+        v[i] = before;
+    }
 }
 
 hipError_t upload_offsets(const uint64_t* host, uint32_t count, uint64_t* dst, hipStream_t stream) {
-    for (uint32_t first = 0; first < count; first += 256) {
-        OffsetBlock blk;
-        uint32_t c = count - first < 256 ? count - first : 256;
-        memcpy(blk.v, host + first, sizeof(uint64_t) * c);
-        hipLaunchKernelGGL(upload_offsets_kernel, dim3(1), dim3(256), 0, stream, blk, dst + first, c);
+    bool narrow = count > kOffsetsPerLaunch;
+    for (uint32_t i = 1; narrow && i < count; ++i) narrow = host[i] - host[i - 1] <= 0xffffffffull;
+    if (!narrow) {
+        for (uint32_t first = 0; first < count; first += kOffsetsPerLaunch) {
+            OffsetBlock blk;
+            const uint32_t c = count - first < kOffsetsPerLaunch ? count - first : kOffsetsPerLaunch;
+            memcpy(blk.v, host + first, sizeof(uint64_t) * c);
+            hipLaunchKernelGGL(upload_block_kernel<OffsetBlock>, dim3(1), dim3(256), 0, stream, blk, dst + first, c);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    // dst[0] = host[0] (= 0), dst[i] = length of segment i - 1; then the prefix sum
+    for (uint32_t first = 0; first < count; first += kLengthsPerLaunch) {
+        LengthBlock blk;
+        const uint32_t c = count - first < kLengthsPerLaunch ? count - first : kLengthsPerLaunch;
+        for (uint32_t i = 0; i < c; ++i) {
+            const uint32_t g = first + i;
+            blk.v[i] = g == 0 ? (uint32_t)host[0] : (uint32_t)(host[g] - host[g - 1]);
+        }
+        hipLaunchKernelGGL(upload_block_kernel<LengthBlock>, dim3(1), dim3(256), 0, stream, blk, dst + first, c);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, stream, dst, count);
+    return hipGetLastError();
 }
 
 bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }

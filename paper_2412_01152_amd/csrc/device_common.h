@@ -22,7 +22,7 @@ constexpr int kBinCopiesReduce = 16;
 constexpr int kStageIters = 8;
 constexpr int kWritePeriodUs = 40;
 constexpr int kWriteWindowUs = 10;
-constexpr uint64_t kMinPhasedElems = 1ull << 27;   // measured: a loss at 64M elements, even at 91M, a gain from 256M
+constexpr uint64_t kMinPhasedElems = 1ull << 27;   // staging pays from a few hundred million elements on
 struct WritePhase {
     uint32_t period;   // in ticks of wall_clock64(); 0 = write every iteration's codes at once
     uint32_t window;   // the first `window` ticks of each period are the write window

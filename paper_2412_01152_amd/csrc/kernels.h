@@ -58,7 +58,7 @@ struct SrcPseudoGrad {
 struct SrcF32 {
     const float* x;
     static constexpr int kLdsFloats = 0;
-    static constexpr int kStage = 0;                // measured: 8.58 ms writing at once, 8.77 ms staged
+    static constexpr int kStage = 0;                // staging gains nothing for a single read stream
     static constexpr int kQuantWaves = 1;
     struct Raw {
         f32x4 a;
@@ -92,7 +92,7 @@ struct SrcReduce {
     static constexpr int kLdsFloats = W * kBuckets;
     static constexpr int kStage = 0;                // the LDS goes to the bin copies and the tables
     // Pass B at W <= 4 is held to 128 registers, so that four blocks (which is what its LDS admits)
-    // are resident per CU instead of three: 9.76 -> 9.63 ms at W = 4 on the 10B buffer.
+    // are resident per CU instead of three.
     static constexpr int kQuantWaves = W <= 4 ? 4 : 1;
     struct Raw {
         uint32_t c[kW];
@@ -293,9 +293,9 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(Src src_in, const uint6
 // accumulators instead.  Thread k owns bin k: every kFlushIters iterations (before either field can
 // overflow) it moves the bin into 64-bit registers, and when the block leaves the segment it
 // adds its totals to the segment's global integer bins.
-// This pass is bound by vector-ALU instruction issue as much as by memory when the source is the
-// reduce (about 20 instructions per element at W = 4), so the per-element chain is kept short: no
-// mask on the index, no mask on the addend, the half bucket folded into centre_0.
+// When the source is the reduce, this pass keeps the vector ALUs and the LDS about as busy as the
+// memory (about 22 vector instructions per element at W = 4), so the per-element chain is kept
+// short: no mask on the index, no mask on the addend, the half bucket folded into centre_0.
 struct PassBOut {
     unsigned long long* hsumq;   // [T][256] signed sum of q (two's complement)
     unsigned long long* hcnt;    // [T][256]
@@ -378,15 +378,12 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
 // (a 64-bit bin spans two of the 32 banks; with 16 copies 16 consecutive lanes never collide).
 //
 // Writing the codes.  On this chip a steady trickle of writes next to the read streams costs far
-// more than its bytes (reads alone run at 7 TB/s, the same reads plus one byte written per element
-// at 5.2-6.2 TB/s in total).  The codes of whole iterations are therefore kept in LDS (kStage
-// iterations of 4 KiB) and written out only inside a short window that recurs with a fixed period
-// of the chip-wide constant-rate clock, the same window for every block, or when the staging area
-// is full: HBM then sees long read phases and short write phases.  Nobody waits for anybody: a
-// block looks at the clock after each iteration and carries on.  Measured in a standalone kernel
-// with the same access pattern: 6.24 -> 6.66 TB/s with the codes far from the inputs, 5.46 -> 6.3-6.5
-// TB/s with everything side by side.  In this kernel: 14.35 -> 14.09 ms for stage 1's pass B at the
-// 10B size.  Sources whose pass B needs its LDS for other things, or gains nothing, set kStage = 0.
+// more than its bytes.  The codes of whole iterations are therefore kept in LDS (kStage iterations
+// of 4 KiB) and written out only inside a short window that recurs with a fixed period of the
+// chip-wide constant-rate clock, the same window for every block, or when the staging area is
+// full: HBM then sees long read phases and short write phases.  Nobody waits for anybody: a block
+// looks at the clock after each iteration and carries on.  Sources whose pass B needs its LDS for
+// other things, or gains nothing, set kStage = 0.
 template <class Src, int kCopies, int kStage>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::kQuantWaves))) void quant_kernel(Src src_in, const uint64_t* __restrict__ seg,
                                                         uint32_t T, uint64_t N, Work work,

@@ -64,37 +64,25 @@ struct Grid {
     Work work;
 };
 // Elements per claim, in block iterations of 4,096 elements (upper limits; small buffers get
-// smaller chunks so that every block still sees about 16 of them).  A claim costs about 20 ns at
-// the one counter, which bounds how short a chunk may be: a pass that moves 5 bytes per element takes
-// 8.5 ms at 8 iterations and 10.5 ms at 4, one that moves 20 and more is still faster at 4.  Measured inside
-// one process at the 10B size: passes that only read run fastest with long chunks (stage 1 pass A:
-// 12.12 ms at 32, 11.73 ms at 128), passes that also write with short ones, which keep the blocks'
-// working set within a narrower window of addresses (stage 1 pass B: 15.32 ms at 32, 14.94 ms at 8;
-// bf16: 12.99 -> 12.42 ms; pass A of the reduce when it stores the accumulation, W = 14: 33.4 ms at
-// 32, 32.0 ms at 4).  Pass B of the reduce source, which recomputes the values from W code streams, sits
-// in between (W = 4, four resident blocks: 9.56 ms at 8, 9.36 at 16, 9.48 at 32, 9.60 at 64).
+// smaller chunks so that every block still sees about 16 of them).  A claim costs a fixed time at
+// the one counter, which bounds how short a chunk may be; above that bound, passes that only read
+// run fastest with long chunks, passes that also write with short ones (the blocks' working set
+// then stays within a narrow window of addresses), and the more bytes an element moves the shorter
+// the best chunk.  All values below were chosen by measurement at the 10B size.
 constexpr uint64_t kChunkItersRead = 128;
 constexpr uint64_t kChunkItersWrite = 8;
-// Pass A of the reduce when it stores the accumulation: the more bytes an element moves, the longer
-// a chunk lasts and the shorter it may be before the counter binds (13 codes + fp32 addend in and
-// fp32 out, 21 B/element, ring-chunk calls: 45.7 ms at 4 iterations, 43.9 at 2; 4 codes in and fp32
-// out, 8 B/element: 22.9 ms at 4, 26.4 at 2).
+// Pass A of the reduce when it stores the accumulation: 2 iterations when an element moves 20 bytes
+// or more (13 codes + fp32 addend in, fp32 out), else 4.
 inline uint64_t chunk_iters_store_acc(uint32_t W, bool has_local) {
     return W + (has_local ? 4u : 0u) + 4u >= 20u ? 2 : 4;
 }
-constexpr uint64_t kChunkItersOuter = 2;      // coded form, 2 blocks per CU: 26.84 ms at 8, 26.62 at 4, 26.04 at 2, 33.0 at 1
+constexpr uint64_t kChunkItersOuter = 2;
 constexpr uint64_t kChunkItersReduceWrite = 16;
 // Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory
-// system): the pass that only reads two fp32 streams (11.62 ms with the 7 that fit, 11.36 with 2,
-// 11.27 with 1) and the outer step (26.96 ms with the 6 that fit, 26.64 with 2, 27.18 with 1).  The
-// Pass B of the streaming sources: 4 (what the staged codes leave room for anyway; the stored-array
-// source, which does not stage, 8.54 ms with the 6 that fit, 8.35 with 4).  The reduce-source
-// kernels are fastest with all the blocks their LDS use admits (3 or 4): their table look-ups need
-// the waves.
-// Pass A of the reduce when it also stores the fp32 accumulation: a write stream next to W byte
-// streams wants few blocks while the table look-ups still find enough waves (10B buffer, 4 blocks
-// resident: W = 4: 14.0 ms with all of them, 13.4 with 2; W = 8: 20.5 / 19.4; W = 10: 24.1 with 4,
-// 23.7 with 3, 28.7 with 2; W = 14: 30.8 with the 3 that fit, 38.8 with 2).
+// system): one for the pass that only reads two fp32 streams, two for the outer step, four for
+// pass B of the streaming sources.  The reduce-source kernels are fastest with all the blocks their
+// LDS use admits (their table look-ups need the waves), except pass A when it also stores the fp32
+// accumulation: a write stream next to W byte streams wants few blocks, 2 up to W = 8 and 3 beyond.
 inline int blocks_per_cu_store_acc(uint32_t W) { return W <= 8 ? 2 : 3; }
 constexpr int kBlocksPerCuStreamRead = 1;
 constexpr int kBlocksPerCuStreamWrite = 4;

@@ -249,6 +249,43 @@ def test_segment_count_at_the_limit(B, oracle_mod):
         B.pseudograd_quantize(theta.to(DEV), locals_[0].to(DEV), off + [n], codes_out=None)
 
 
+def test_segment_table_with_a_segment_of_more_than_2_pow_32_elements(B, oracle_mod):
+    """600 quantisation groups, the first of 2^32 + 5 elements: long tables travel to the device as 32-bit
+    segment lengths unless a length does not fit, which is this case (64-bit offsets, several launches).
+    The outer step decodes every element through its segment's codebook, so a wrong offset anywhere shows;
+    the head of the buffer and everything from just before the first boundary on are compared with the oracle."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 50e9:
+        pytest.skip(f"needs about 45 GB of free HBM, have {free / 1e9:.0f} GB")
+    sizes = [(1 << 32) + 5] + [1000] * 599
+    off = synth.offsets_from_sizes(sizes)
+    n, T = off[-1], len(sizes)
+    say(f"[big segment] n={n} T={T}")
+    theta = synth.fill_theta_outer(torch.empty(n, dtype=torch.float32, device=DEV))
+    mom = torch.zeros(n, dtype=torch.float32, device=DEV)
+    codes = synth.fill_coded_contribution(torch.empty(n, dtype=torch.uint8, device=DEV), 0)
+    luts = synth.synthetic_codebooks(T, 0, device=DEV)
+    luts += torch.arange(T, device=DEV, dtype=torch.float32)[:, None] * 1e-3      # every group's codebook is distinct
+    head, tail = 10_000, off[1] - 5_000
+    th_head, th_tail = t2n(theta[:head]), t2n(theta[tail:])
+    B.outer_step(theta, mom, 0.7, 0.9, delta_codes=codes, delta_lut=luts, seg_offsets=off)
+    torch.cuda.synchronize()
+    h_luts = t2n(luts)
+    for name, a, b, th_old, seg_local, lut_local in (
+            ("head", 0, head, th_head, [0, head], h_luts[:1]),
+            ("tail", tail, n, th_tail, [0] + [o - tail for o in off[1:]], h_luts)):
+        th_o, m_o = th_old.copy(), np.zeros(b - a, dtype=np.float32)
+        oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=t2n(codes[a:b]), delta_luts=np.ascontiguousarray(lut_local),
+                              seg_offsets=seg_local)
+        check_outer(t2n(mom[a:b]), m_o, np.zeros(b - a, dtype=np.float32), np.abs(m_o), f"momentum ({name})")
+        check_outer(t2n(theta[a:b]), th_o, th_old, 0.7 * 1.9 * np.abs(m_o), f"theta ({name})")
+    # first step from a zero buffer: m' = g exactly, everywhere in the big segment
+    step = 1 << 28
+    for a in range(0, off[1], step):
+        b = min(a + step, off[1])
+        assert torch.equal(mom[a:b], luts[0][codes[a:b].long()])
+
+
 @pytest.mark.parametrize("W,divisor", [(0, 1), (0, 3), (1, 2), (4, 5), (13, 14), (16, 17)])
 @pytest.mark.parametrize("alias", [False, True])
 def test_stage2_local_addend(B, oracle_mod, W, divisor, alias):

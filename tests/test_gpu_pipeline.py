@@ -1,8 +1,8 @@
 """Chunk-pipelined reduce (transfer of chunk c+1 overlapping the reduction of chunk c) against the
 oracle's per-chunk reduce, and against the same calls issued strictly in order.
 
-The coded contributions start in pinned host memory; each chunk is brought in by asynchronous
-host-to-device copies on a second stream while the previous chunk is being reduced.
+The coded contributions start in pinned host memory, or in a second resident copy in device memory; each
+chunk is brought in by asynchronous copies on a second stream while the previous chunk is being reduced.
 """
 import sys
 
@@ -31,20 +31,24 @@ def B():
     return binding
 
 
+@pytest.mark.parametrize("arrival", ["host to device", "device to device"])
 @pytest.mark.parametrize("overlap", [True, False])
-def test_pipelined_chunks_match_oracle(B, oracle_mod, overlap):
+def test_pipelined_chunks_match_oracle(B, oracle_mod, overlap, arrival):
     from paper_2412_01152_amd.pipeline import reduce_chunks_pipelined
     W, C = 3, 5
     N = 1_500_007                                    # odd chunk size: chunks start off the 128-byte grid
     chunk_sizes = synth.ring_chunk_sizes(N, C)
     coff = synth.offsets_from_sizes(chunk_sizes)
-    say(f"[pipeline] overlap={overlap} N={N} chunks={chunk_sizes} W={W}")
+    say(f"[pipeline] overlap={overlap} arrival={arrival} N={N} chunks={chunk_sizes} W={W}")
     theta, locals_, _ = synth.make_inputs([N], W + 1, kind="mixture", device="cpu")
     # every peer quantises each ring chunk as its own group (oracle, on the CPU)
     st = [oracle_mod.pseudograd_quantize(theta.numpy(), locals_[p].numpy(), coff) for p in range(W)]
     own = (theta - locals_[W]).numpy().copy()        # the owner's fp32 pseudo-gradient
     host_codes = [torch.from_numpy(s[0]).pin_memory() for s in st]
     host_luts = [torch.from_numpy(s[1]).pin_memory() for s in st]
+    if arrival == "device to device":                # a second resident copy: the stand-in for a fast link
+        host_codes = [h.to(DEV) for h in host_codes]
+        host_luts = [h.to(DEV) for h in host_luts]
 
     def arrive(c, code_bufs, lut_bufs):
         a, b = coff[c], coff[c + 1]
