@@ -347,13 +347,7 @@ def run_step_benchmark(args, np, torch, B, synth, dev, cfg, want_extras):
         step()
     torch.cuda.synchronize()
     if args.calibrate_copy:
-        n_cal = 1 << 28                      # 1 GiB read + 1 GiB written, one launch
-        src = local[:n_cal]
-        dst = torch.empty(n_cal, dtype=torch.float32, device=dev)
-        for _ in range(3):
-            torch.neg(src, out=dst)          # the only negation kernel in the run: easy to find
-        torch.cuda.synchronize()
-        del dst
+        calibration_copy(torch, local, alloc)
 
     # HIP events: created by torch (one dummy record makes the handle exist), recorded by the library
     def make_events():
@@ -597,6 +591,17 @@ def study_quantiser(args, np, torch, B, synth, dev):
     print(json.dumps({"study": "quantiser variants", "elements": N, "rows": rows}), flush=True)
 
 
+def calibration_copy(torch, src_buf, alloc):
+    """A plain elementwise copy of known traffic (2^28 fp32: 1 GiB read + 1 GiB written per launch) for
+    scaling a profiler's byte counters; torch.neg is the only negation kernel in a run, so it is easy to find."""
+    n_cal = 1 << 28
+    dst = alloc(n_cal, torch.float32)
+    for _ in range(3):
+        torch.neg(src_buf[:n_cal], out=dst)
+    torch.cuda.synchronize()
+    del dst
+
+
 def measure_copy_kernel(torch, src_buf, alloc):
     """Bandwidth of a plain elementwise copy (read 4 B, write 4 B per element) of up to 2^30 fp32, measured
     in this process: the nominal 8 TB/s is never reached by any kernel, so the step is also
@@ -676,6 +681,8 @@ def measure_config3(args, np, torch, B, synth, dev, alloc, steps, warmup):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        calibration_copy(torch, theta, alloc)
     evs = []
     for _ in range(steps):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -764,6 +771,8 @@ def measure_config4(args, np, torch, B, synth, dev, alloc, steps, warmup):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        calibration_copy(torch, theta, alloc)
     t_start = time.perf_counter()
     for _ in range(steps):
         step()

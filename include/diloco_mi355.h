@@ -260,6 +260,24 @@ int32_t diloco_ring_order(const double* bandwidth, uint32_t n, uint32_t* order_o
                           double* bottleneck_out);
 
 /*
+ * Placement advice for callers that own one large device allocation (host arithmetic only).
+ * On an MI355X the streaming kernels run 2 to 8 % faster when a buffer that a kernel WRITES does not lie
+ * within about 64 GiB of the buffers the same kernel reads or updates (measured; it does not depend on the
+ * low address bits).  Buffers of a few GiB that an allocator hands out one after the other all lie side by
+ * side, which is the slow case; buffers of tens of GiB are far apart by themselves.  This call returns, for
+ * an arena of arena_bytes, the byte offsets at which to start carving three groups of buffers:
+ *     offsets_out[0]  "read"   what the three calls only read, or update in place while reading:
+ *                              theta_outer, theta_local, the peers' codes
+ *     offsets_out[1]  "state"  momentum, and the codes that diloco_pseudograd_quantize writes
+ *     offsets_out[2]  "out"    the codes that int8_reduce_chunk writes (and outer_nesterov_step reads)
+ * The groups start 100 GiB apart when the arena has room for that (216 GiB or more), else a third of
+ * the arena apart; offsets are multiples of 4096.  Results never depend on placement.
+ *   offsets_out  HOST, [3]
+ * Returns DILOCO_OK, DILOCO_ERR_NULL, or DILOCO_ERR_SIZE (an arena below 12 KiB).
+ */
+int32_t diloco_placement(uint64_t arena_bytes, uint64_t* offsets_out);
+
+/*
  * Instrumentation for benchmarks (not part of the method).  After this call, every later call of
  * the three operations made from the same host thread records HIP events on its stream around its
  * streaming kernels, so a harness can time each kernel without a profiler:

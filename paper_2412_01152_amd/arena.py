@@ -56,11 +56,10 @@ def role_bases(arena: Arena) -> Dict[str, int]:
                theta_local, the peers' codes
       "state"  momentum and the codes stage 1 writes
       "out"    the codes stage 2 writes (and the outer step reads)
-    Offsets in bytes into the arena; carve with carve(..., at=base) for the first buffer of a group."""
-    third = arena.nbytes // 3 // ALIGN * ALIGN
-    gap = 100 * GiB if arena.nbytes >= 216 * GiB else third       # the spacing that was measured, if it fits
-    lead = min(4 * GiB, third // 8) // ALIGN * ALIGN
-    return {"read": lead, "state": lead + gap, "out": lead + 2 * gap}
+    Offsets in bytes into the arena; carve with carve(..., at=base) for the first buffer of a group.
+    The rule itself is the library's (diloco_placement); this only names the three results."""
+    read, state, out = B.placement(arena.nbytes)
+    return {"read": read, "state": state, "out": out}
 
 
 def place_outer_state(arena: Arena, N: int, seg_offsets: Sequence[int], shifts_gib: Sequence[int],

@@ -32,7 +32,7 @@ assert QPARAMS_DTYPE.itemsize == QPARAMS_BYTES
 EXPORTS = ("diloco_workspace_bytes", "diloco_strerror", "diloco_pseudograd_quantize",
            "int8_reduce_chunk", "outer_nesterov_step", "diloco_profile_passes",
            "diloco_pseudograd_quantize_variant", "int8_reduce_chunk_variant", "diloco_ring_order",
-           "diloco_tune_write_phase", "int8_reduce_chunk_static")
+           "diloco_tune_write_phase", "int8_reduce_chunk_static", "diloco_placement")
 
 CODEBOOK_MEAN, CODEBOOK_MIDPOINT = 0, 1
 
@@ -77,6 +77,8 @@ def load() -> ctypes.CDLL:
     lib.outer_nesterov_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u64, f32, f32, vp, i32, vp, sz, vp]
     lib.diloco_profile_passes.restype = i32
     lib.diloco_profile_passes.argtypes = [vp]
+    lib.diloco_placement.restype = i32
+    lib.diloco_placement.argtypes = [u64, vp]
     lib.diloco_tune_write_phase.restype = i32
     lib.diloco_tune_write_phase.argtypes = [i32, i32]
     _lib = lib
@@ -99,6 +101,15 @@ def tune_write_phase(period_us: int, window_us: int = 0) -> None:
     rc = load().diloco_tune_write_phase(ctypes.c_int32(period_us), ctypes.c_int32(window_us))
     if rc != 0:
         raise DilocoError(rc, "diloco_tune_write_phase")
+
+
+def placement(arena_bytes: int) -> Tuple[int, int, int]:
+    """diloco_placement: byte offsets of the "read", "state" and "out" groups in an arena of arena_bytes."""
+    out = (ctypes.c_uint64 * 3)()
+    rc = load().diloco_placement(ctypes.c_uint64(arena_bytes), ctypes.cast(out, ctypes.c_void_p))
+    if rc != 0:
+        raise DilocoError(rc, "diloco_placement")
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 def workspace_bytes(T: int) -> int:

@@ -416,6 +416,21 @@ int32_t diloco_profile_passes(void* const* events) {
     return DILOCO_OK;
 }
 
+int32_t diloco_placement(uint64_t arena_bytes, uint64_t* offsets_out) {
+    if (!offsets_out) return DILOCO_ERR_NULL;
+    constexpr uint64_t kGiB = 1ull << 30, kAlign = 4096;
+    if (arena_bytes < 3 * kAlign) return DILOCO_ERR_SIZE;
+    const uint64_t third = arena_bytes / 3 / kAlign * kAlign;
+    // the spacing at which the measured dependence on distance has levelled off, if the arena is large
+    // enough for three groups that far apart; else a third of the arena
+    const uint64_t gap = arena_bytes >= 216 * kGiB ? 100 * kGiB : third;
+    const uint64_t lead = std::min<uint64_t>(4 * kGiB, third / 8) / kAlign * kAlign;
+    offsets_out[0] = lead;
+    offsets_out[1] = lead + gap;
+    offsets_out[2] = lead + 2 * gap;
+    return DILOCO_OK;
+}
+
 int32_t diloco_tune_write_phase(int32_t period_us, int32_t window_us) {
     if (period_us < 0) {                                  // back to the built-in choice by size
         g_write_phase_override.store(0, std::memory_order_relaxed);

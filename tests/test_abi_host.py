@@ -114,6 +114,19 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert o(vp(0x1001), fake, fake, vp(0), vp(0), vp(0), 0, 16, f(.7), f(.9), vp(0), 0, vp(0), 0, vp(0)) == -3
 
 
+def test_placement_advice(lib):
+    """diloco_placement: three group offsets, 100 GiB apart in a large arena, a third apart in a small one."""
+    from paper_2412_01152_amd import binding
+    GiB = 1 << 30
+    r = binding.placement(280 * GiB)
+    assert r == (4 * GiB, 104 * GiB, 204 * GiB)
+    r = binding.placement(3 * GiB)
+    assert r[1] - r[0] == r[2] - r[1] == GiB and all(v % 4096 == 0 for v in r) and r[2] + GiB // 2 < 3 * GiB
+    out = (ctypes.c_uint64 * 3)()
+    assert lib.diloco_placement(ctypes.c_uint64(100), ctypes.cast(out, ctypes.c_void_p)) == -2
+    assert lib.diloco_placement(ctypes.c_uint64(GiB), ctypes.c_void_p(0)) == -1
+
+
 def test_write_phase_tuning_validates_its_arguments(lib):
     """The instrumentation call that retimes pass B's staged code writes: host state only, no device use."""
     t = lib.diloco_tune_write_phase
