@@ -208,7 +208,8 @@ hipError_t finalize_lut(const Pass& p, const QuantVariant& v, const diloco_qpara
 
 template <class Src>
 hipError_t run_stats(const Src& src, const Pass& p, uint32_t phase) {
-    hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + 255) / 256), dim3(256), 0, p.stream, src, p.seg, p.T,
+    hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + kPivotSegmentsPerBlock - 1) / kPivotSegmentsPerBlock),
+                       dim3(kThreads), 0, p.stream, src, p.seg, p.T,
                        p.pivot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -169,20 +169,23 @@ struct SrcReduce {
 // pass may overwrite its own input (accumulation stored in place over the local addend).
 // One pair of fp64 atomics per (block, segment).  When kWriteAcc, the values are also stored.
 constexpr int kPivotSamples = 9;
+constexpr int kPivotLanes = 16;                      // lanes per segment (the first nine take a sample each)
+constexpr int kPivotSegmentsPerBlock = kThreads / kPivotLanes;
 template <class Src>
-__global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t T,
-                             float* __restrict__ pivot) {
-    uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= T) return;
-    const uint64_t a = seg[s], n = seg[s + 1] - a;
-    if (n == 0) {
-        pivot[s] = 0.0f;
-        return;
+__global__ __launch_bounds__(kThreads) void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t T,
+                                                        float* __restrict__ pivot) {
+    const uint32_t s = blockIdx.x * kPivotSegmentsPerBlock + threadIdx.x / kPivotLanes;
+    const int j = threadIdx.x % kPivotLanes;
+    uint64_t a = 0, n = 0;
+    if (s < T) {
+        a = seg[s];
+        n = seg[s + 1] - a;
     }
+    float mine = 0.0f;
+    if (n > 0 && j < kPivotSamples) mine = src.sample_value(a + (uint64_t)j * (n - 1) / (kPivotSamples - 1), s);
     float v[kPivotSamples];
 #pragma unroll
-    for (int j = 0; j < kPivotSamples; ++j)
-        v[j] = src.sample_value(a + (uint64_t)j * (n - 1) / (kPivotSamples - 1), s);
+    for (int i = 0; i < kPivotSamples; ++i) v[i] = __shfl(mine, i, kPivotLanes);
     // odd-even transposition sort, fully unrolled (a NaN sample drops out: fminf / fmaxf return the
     // other operand; the statistics pass itself still sees it and the segment is flagged)
 #pragma unroll
@@ -194,7 +197,7 @@ __global__ void pivot_kernel(Src src, const uint64_t* __restrict__ seg, uint32_t
             v[i + 1] = hi;
         }
     }
-    pivot[s] = v[kPivotSamples / 2];
+    if (s < T && j == 0) pivot[s] = n > 0 ? v[kPivotSamples / 2] : 0.0f;
 }
 
 template <class Src, bool kWriteAcc>

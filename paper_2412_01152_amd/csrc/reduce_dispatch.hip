@@ -30,7 +30,8 @@ SrcReduce<W, kLocal, kTrueDiv> make_src(const ReduceArgs& a) {
 template <int W, bool kLocal, bool kTrueDiv, bool kWriteAcc>
 hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
-    hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + 255) / 256), dim3(256), 0, p.stream,
+    hipLaunchKernelGGL(pivot_kernel<Src>, dim3((p.T + kPivotSegmentsPerBlock - 1) / kPivotSegmentsPerBlock),
+                       dim3(kThreads), 0, p.stream,
                        make_src<W, kLocal, kTrueDiv>(a), p.seg, p.T, p.pivot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
