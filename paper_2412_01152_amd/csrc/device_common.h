@@ -139,6 +139,15 @@ struct Work {
 struct Share {
     uint64_t begin, end;
 };
+// The element range of claim c (c < w.num_chunks): chunk 0 starts at element 0 and also takes the
+// elements in front of the origin, chunk c >= 1 starts at origin + c * chunk.
+__host__ __device__ __forceinline__ Share claim_range(const Work& w, unsigned long long c, uint64_t N) {
+    Share sh;
+    sh.begin = c ? w.origin + c * w.chunk : 0;
+    const uint64_t e = w.origin + (c + 1) * w.chunk;
+    sh.end = e < N ? e : N;
+    return sh;
+}
 struct Claimer {
     unsigned long long next;
     __device__ __forceinline__ explicit Claimer(const Work& w) : next(blockIdx.x) {
@@ -155,9 +164,7 @@ struct Claimer {
             next += gridDim.x;
         else if (threadIdx.x == 0)
             next = atomicAdd(w.counter, 1ull);
-        sh.begin = c ? w.origin + c * w.chunk : 0;
-        const uint64_t e = w.origin + (c + 1) * w.chunk;
-        sh.end = e < N ? e : N;
+        sh = claim_range(w, c, N);
         return true;
     }
 };
