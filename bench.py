@@ -1018,6 +1018,15 @@ def time_extras(torch, B, theta, local, mom, peer_codes, peer_luts, codes1, lut1
     timed("stage1 bf16 theta_local (13 B/elem)", 13,
           lambda: B.pseudograd_quantize(theta, local_bf16, off, codes_out=codes1, lut_out=lut1, qparams_out=qp,
                                         workspace=ws))
+    # the quantiser with bucket midpoints instead of bucket averages as its codebook (a variant the paper argues
+    # against in words): pass B then needs no bucket sums, so no LDS atomics and no offset arithmetic
+    timed("stage1 fp32, midpoint codebook (17 B/elem)", 17,
+          lambda: B.pseudograd_quantize(theta, local, off, codes_out=codes1, lut_out=lut1, qparams_out=qp,
+                                        workspace=ws, variant=(6.0, B.CODEBOOK_MIDPOINT)))
+    timed(f"stage2 W={W}, midpoint codebook ({2 * W + 1} B/elem)", 2 * W + 1,
+          lambda: B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp,
+                                 workspace=ws, variant=(6.0, B.CODEBOOK_MIDPOINT)))
+    B.reduce_chunk(peer_codes, peer_luts, off, W, codes_out=codes2, lut_out=lut2, qparams_out=qp, workspace=ws)
     timed("stage3 coded + bf16 hand-back (19 B/elem)", 19,
           lambda: B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off,
                                theta_local_out=handback_bf16, workspace=ws))

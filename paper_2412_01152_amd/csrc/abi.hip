@@ -152,7 +152,7 @@ int32_t num_compute_units(int* out) {
 
 // Uploads the offsets, clears the accumulators, and fills in the Pass record.
 int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, void* workspace,
-                   size_t workspace_bytes, hipStream_t stream) {
+                   size_t workspace_bytes, hipStream_t stream, bool bins) {
     if (!workspace) return DILOCO_ERR_NULL;
     if (misaligned(workspace, 256)) return DILOCO_ERR_ALIGN;
     const WorkspaceLayout L = workspace_layout(T);
@@ -169,6 +169,7 @@ int32_t begin_pass(Pass& p, uint64_t N, uint32_t T, const uint64_t* seg_host, vo
     p.ocnt = (unsigned long long*)(ws + L.ocnt);
     p.counters = (unsigned long long*)(ws + L.counters);
     p.stream = stream;
+    p.bins = bins;
     int32_t rc = num_compute_units(&p.num_cus);
     if (rc) return rc;
     p.write_phase = choose_write_phase(N);
@@ -223,9 +224,9 @@ hipError_t run_stats(const Src& src, const Pass& p, uint32_t phase) {
     return e;
 }
 
-template <class Src>
-hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
-    constexpr auto kernel = quant_kernel<Src, kBinCopiesStream, Src::kStage>;
+template <class Src, int kCopies>
+hipError_t run_quant_as(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    constexpr auto kernel = quant_kernel<Src, kCopies, Src::kStage>;
     Grid g = plan_grid(p.N, p.num_cus, std::min(resident_blocks_per_cu<kernel>(), kBlocksPerCuStreamWrite),
                        p.counters + 1, host_phase(codes, 1), kChunkItersWrite);
     (void)mark(2, p.stream);
@@ -234,6 +235,10 @@ hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, ui
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
+}
+template <class Src>
+hipError_t run_quant(const Src& src, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    return p.bins ? run_quant_as<Src, kBinCopiesStream>(src, p, qp, codes) : run_quant_as<Src, 0>(src, p, qp, codes);
 }
 
 hipError_t reduce_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
@@ -337,7 +342,7 @@ int32_t pseudograd_quantize_impl(const float* theta_outer, const void* theta_loc
         misaligned(lut_out, 4) || misaligned(qparams_out, 8))
         return DILOCO_ERR_ALIGN;
     Pass p;
-    rc = begin_pass(p, N, T, seg_offsets, workspace, workspace_bytes, stream);
+    rc = begin_pass(p, N, T, seg_offsets, workspace, workspace_bytes, stream, v.codebook == DILOCO_CODEBOOK_MEAN);
     if (rc) return rc;
     if (local_dtype == DILOCO_DTYPE_BF16) {
         SrcPseudoGrad<true> src{theta_outer, theta_local};
@@ -386,7 +391,7 @@ int32_t reduce_chunk_impl(const uint8_t* const* peer_codes, const float* const* 
         a.div = (float)divisor;
     }
     Pass p;
-    rc = begin_pass(p, n, T, seg_offsets, workspace, workspace_bytes, stream);
+    rc = begin_pass(p, n, T, seg_offsets, workspace, workspace_bytes, stream, v.codebook == DILOCO_CODEBOOK_MEAN);
     if (rc) return rc;
     if (n) DILOCO_TRY(reduce_stats(a, p, acc_out));
     DILOCO_TRY(finalize_qparams(p, v, qparams_out));

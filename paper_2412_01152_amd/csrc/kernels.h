@@ -376,9 +376,23 @@ __device__ __forceinline__ uint32_t code_and_bin4(f32x4 v, const BinScale& b, un
     return (uint32_t)k[0] | ((uint32_t)k[1] << 8) | ((uint32_t)k[2] << 16) | ((uint32_t)k[3] << 24);
 }
 
+// The bucket indices alone, for a codebook that needs no bucket sums (bucket midpoints).
+__device__ __forceinline__ int code_only(float x, const BinScale& b) {
+    return (int)(unsigned)bucket_of_f(x, b.lo, b.inv_w);
+}
+__device__ __forceinline__ uint32_t code_only4(f32x4 v, const BinScale& b) {
+    uint32_t k[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) k[e] = (uint32_t)bucket_of_f(v[e], b.lo, b.inv_w);
+    return k[0] | (k[1] << 8) | (k[2] << 16) | (k[3] << 24);
+}
+
 // kCopies: each bucket's LDS bin exists kCopies times, copy (lane mod kCopies) at consecutive
 // addresses, so that neighbouring lanes hit different banks even when they hit the same bucket
 // (a 64-bit bin spans two of the 32 banks; with 16 copies 16 consecutive lanes never collide).
+// kCopies == 0: no bins at all - the pass only writes codes (the midpoint codebook of the quantiser
+// variants is a function of the range alone), which takes the LDS atomics, the offset arithmetic and
+// the flushes out of the loop.
 //
 // Writing the codes.  On this chip a steady trickle of writes next to the read streams costs far
 // more than its bytes.  The codes of whole iterations are therefore kept in LDS (kStage iterations
@@ -394,7 +408,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
                                                         uint8_t* __restrict__ codes, PassBOut out,
                                                         WritePhase phase_cfg) {
     __shared__ float s_src[Src::kLdsFloats > 0 ? Src::kLdsFloats : 1];
-    __shared__ unsigned long long s_bin_all[kBuckets * kCopies];
+    constexpr bool kBins = kCopies > 0;
+    __shared__ unsigned long long s_bin_all[kBins ? kBuckets * kCopies : 1];
     __shared__ double s_red[8];
     __shared__ unsigned long long s_claim;
     // staged codes and the element index each staged iteration starts at (kStage == 0: no staging)
@@ -404,7 +419,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
     Src src = src_in;
     src.bind(s_src);
     const int tid = threadIdx.x;
-    unsigned long long* const s_bin = s_bin_all + (tid & (kCopies - 1));   // this lane's copy
+    unsigned long long* const s_bin = s_bin_all + (kBins ? (tid & (kCopies - 1)) : 0);   // this lane's copy
     const uint32_t phase = work.phase;
     // Bins and totals live across the block's chunks for as long as the segment stays the same: the
     // LDS bins are drained into registers before either of their fields can overflow, and the registers
@@ -426,14 +441,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
         __syncthreads();
         staged = 0;
     };
+    if constexpr (kBins) {
 #pragma unroll
-    for (int c = 0; c < kCopies; ++c) s_bin_all[c * kBuckets + tid] = 0;
-    __syncthreads();
+        for (int c = 0; c < kCopies; ++c) s_bin_all[c * kBuckets + tid] = 0;
+        __syncthreads();
+    }
     // thread k sums and clears the kCopies copies of bin k, starting at a rotated copy so that the
     // lanes of a wave read different banks; callers put a barrier before and after
     auto drain = [&]() {
 #pragma unroll
-        for (int i = 0; i < kCopies; ++i) {
+        for (int i = 0; i < (kBins ? kCopies : 0); ++i) {
             const int idx = tid * kCopies + ((i + tid) & (kCopies - 1));
             const unsigned long long packed = s_bin_all[idx];
             s_bin_all[idx] = 0;
@@ -444,6 +461,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
         pending = 0;
     };
     auto flush_segment = [&]() {                 // block-uniform
+        if constexpr (!kBins) return;
         __syncthreads();
         drain();
         if (bin_c) {
@@ -489,11 +507,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
             }
             auto single = [&](uint64_t lo, uint64_t hi) {
                 for (uint64_t i = lo + tid; i < hi; i += kThreads)
-                    codes[i] = (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far);
+                    codes[i] = kBins ? (uint8_t)code_and_bin(src.value1(i), bs, s_bin, kCopies, far)
+                                     : (uint8_t)code_only(src.value1(i), bs);
                 pending += (uint32_t)(hi - lo);
             };
             auto drain_if_due = [&]() {
-                if (pending >= kDrainAfter) {
+                if (kBins && pending >= kDrainAfter) {
                     __syncthreads();
                     drain();
                     __syncthreads();
@@ -509,7 +528,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Src::k
 #pragma unroll
                 for (int j = 0; j < kUnroll; ++j) {
                     const f32x4 v = src.value4(raw[j]);
-                    const uint32_t packed = code_and_bin4(v, bs, s_bin, kCopies, far);
+                    const uint32_t packed = kBins ? code_and_bin4(v, bs, s_bin, kCopies, far) : code_only4(v, bs);
                     if (phased)
                         s_stage[staged * (kIter / 4) + j * kThreads + tid] = packed;
                     else

@@ -22,6 +22,7 @@ struct Pass {
     unsigned long long* counters;   // device, [kNumCounters], zero at the start of the call
     int num_cus;
     WritePhase write_phase;     // when pass B writes its staged codes
+    bool bins;                  // pass B also sums the buckets (false: the codebook needs no sums)
     hipStream_t stream;
 };
 

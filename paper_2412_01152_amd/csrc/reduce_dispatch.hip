@@ -50,10 +50,10 @@ hipError_t run_stats(const ReduceArgs& a, const Pass& p, float* acc_out) {
     return e;
 }
 
-template <int W, bool kLocal, bool kTrueDiv>
-hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+template <int W, bool kLocal, bool kTrueDiv, int kCopies>
+hipError_t run_quant_as(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
-    constexpr auto kernel = quant_kernel<Src, kBinCopiesReduce, Src::kStage>;
+    constexpr auto kernel = quant_kernel<Src, kCopies, Src::kStage>;
     Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
                        kChunkItersReduceWrite);
     (void)mark(2, p.stream);
@@ -62,6 +62,12 @@ hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* q
     hipError_t e = hipGetLastError();
     (void)mark(3, p.stream);
     return e;
+}
+
+template <int W, bool kLocal, bool kTrueDiv>
+hipError_t run_quant(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
+    return p.bins ? run_quant_as<W, kLocal, kTrueDiv, kBinCopiesReduce>(a, p, qp, codes)
+                  : run_quant_as<W, kLocal, kTrueDiv, 0>(a, p, qp, codes);
 }
 
 template <int W, bool kLocal, bool kTrueDiv>
