@@ -79,6 +79,7 @@ inline uint64_t chunk_iters_store_acc(uint32_t W, bool has_local) {
 }
 constexpr uint64_t kChunkItersOuter = 2;
 constexpr uint64_t kChunkItersReduceWrite = 16;
+constexpr uint64_t kChunkItersReduceNoBins = 8;      // pass B of the reduce when the codebook needs no bucket sums
 // Blocks per compute unit where fewer than fit run faster (fewer concurrent streams for the memory
 // system): one for the pass that only reads two fp32 streams, two for the outer step, four for
 // pass B of the streaming sources.  The reduce-source kernels are fastest with all the blocks their
@@ -88,6 +89,7 @@ inline int blocks_per_cu_store_acc(uint32_t W) { return W <= 8 ? 2 : 3; }
 constexpr int kBlocksPerCuStreamRead = 1;
 constexpr int kBlocksPerCuStreamWrite = 4;
 constexpr int kBlocksPerCuOuter = 2;
+constexpr int kBlocksPerCuReduceNoBins = 3;
 inline uint32_t host_phase(const void* p, int elem_bytes) {
     return (uint32_t)((uintptr_t)p / (uintptr_t)elem_bytes) & (kAlignElems - 1);
 }

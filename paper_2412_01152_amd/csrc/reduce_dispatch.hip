@@ -54,8 +54,12 @@ template <int W, bool kLocal, bool kTrueDiv, int kCopies>
 hipError_t run_quant_as(const ReduceArgs& a, const Pass& p, const diloco_qparams* qp, uint8_t* codes) {
     using Src = SrcReduce<W, kLocal, kTrueDiv>;
     constexpr auto kernel = quant_kernel<Src, kCopies, Src::kStage>;
-    Grid g = plan_grid(p.N, p.num_cus, resident_blocks_per_cu<kernel>(), p.counters + 1, host_phase(codes, 1),
-                       kChunkItersReduceWrite);
+    // with bins the look-ups and LDS atomics need every wave that fits; without them the memory side
+    // decides, and it prefers fewer blocks and shorter chunks (a narrower window of active addresses)
+    const int bpc = kCopies > 0 ? resident_blocks_per_cu<kernel>()
+                                : std::min(resident_blocks_per_cu<kernel>(), kBlocksPerCuReduceNoBins);
+    Grid g = plan_grid(p.N, p.num_cus, bpc, p.counters + 1, host_phase(codes, 1),
+                       kCopies > 0 ? kChunkItersReduceWrite : kChunkItersReduceNoBins);
     (void)mark(2, p.stream);
     hipLaunchKernelGGL(kernel, dim3(g.blocks), dim3(kThreads), 0, p.stream, make_src<W, kLocal, kTrueDiv>(a), p.seg,
                        p.T, p.N, g.work, qp, codes, PassBOut{p.hsumq, p.hcnt, p.osum, p.ocnt}, p.write_phase);
