@@ -249,6 +249,27 @@ def test_segment_count_at_the_limit(B, oracle_mod):
         B.pseudograd_quantize(theta.to(DEV), locals_[0].to(DEV), off + [n], codes_out=None)
 
 
+@pytest.mark.parametrize("T", [479, 480, 481, 959, 960, 961, 1920, 1921])
+def test_segment_table_sizes_around_the_launch_limits(B, oracle_mod, T):
+    """A table of up to 480 offsets goes up in one launch; longer ones as 32-bit lengths, 960 per launch,
+    followed by a prefix sum: table sizes on both sides of every limit, stage 1 and the coded outer step."""
+    rng = np.random.default_rng(T)
+    sizes = rng.integers(0, 300, size=T).tolist()
+    sizes[0], sizes[T - 1] = 5000, 4097
+    theta, locals_, off = synth.make_inputs(sizes, 1, device=DEV)
+    codes, luts, qp = _check_stage1(B, oracle_mod, theta, locals_[0], off, f"T={T}")
+    o_codes, o_luts, _, _ = oracle_mod.pseudograd_quantize(t2n(theta), t2n(locals_[0]), off)
+    n = off[-1]
+    th_o, m_o = t2n(theta).copy(), np.zeros(n, dtype=np.float32)
+    th_t, m_t = theta.clone(), torch.zeros(n, dtype=torch.float32, device=DEV)
+    B.outer_step(th_t, m_t, 0.7, 0.9, delta_codes=torch.from_numpy(o_codes).to(DEV),
+                 delta_lut=torch.from_numpy(o_luts).to(DEV), seg_offsets=off)
+    oracle_mod.outer_step(th_o, m_o, 0.7, 0.9, delta_codes=o_codes, delta_luts=o_luts, seg_offsets=off)
+    torch.cuda.synchronize()
+    check_outer(t2n(m_t), m_o, np.zeros(n, dtype=np.float32), np.abs(m_o), "momentum")
+    check_outer(t2n(th_t), th_o, t2n(theta), 0.7 * 1.9 * np.abs(m_o), "theta")
+
+
 def test_segment_table_with_a_segment_of_more_than_2_pow_32_elements(B, oracle_mod):
     """600 quantisation groups, the first of 2^32 + 5 elements: long tables travel to the device as 32-bit
     segment lengths unless a length does not fit, which is this case (64-bit offsets, several launches).
