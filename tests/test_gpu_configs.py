@@ -29,6 +29,8 @@ LR, BETA = 0.7, 0.9
 def say(msg):
     print(msg, flush=True)
     sys.stdout.flush()
+    from conftest import progress
+    progress(msg)
 
 
 @pytest.fixture(scope="module")
@@ -276,6 +278,106 @@ def test_config2_fullsize_sampled_tensors(B, oracle_mod):
     g = lut2[5][codes2[a:b].long()]
     assert torch.equal(mom[a:b], g)
     say(f"[config2] stage 3 checked; total one-bucket flips on sampled tensors: {flips}")
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 2 at full size, EVERY element of all three stages against the oracle: stage 1 on this
+# worker's 10,211,381,248 pseudo-gradient values, the reduce of its codes with three more coded
+# contributions, the outer step from the oracle's requantised result.  (The other three contributions
+# are synthetic codes and codebooks, so that the host runs stage 1 once, not four times.)
+# ---------------------------------------------------------------------------------------------
+
+def test_config2_fullsize_every_element_against_the_oracle(B, oracle_mod):
+    import psutil
+    sizes = synth.config_segment_sizes(2)
+    off = synth.offsets_from_sizes(sizes)
+    N, T, W = off[-1], len(sizes), 4
+    free, _ = torch.cuda.mem_get_info()
+    if free < 190e9:
+        pytest.skip(f"needs about 185 GB of free HBM, have {free / 1e9:.0f} GB")
+    if psutil.virtual_memory().available < 175e9:
+        pytest.skip(f"needs about 140 GB of host memory, {psutil.virtual_memory().available / 1e9:.0f} GB available")
+    t_all = time.time()
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local = synth.fill_theta_local(torch.empty(N, dtype=torch.float32, device=DEV), theta, 0, "mixture")
+    ws = B.new_workspace(T, DEV)
+    codes1, lut1, qp1 = B.pseudograd_quantize(theta, local, off, workspace=ws)
+    torch.cuda.synchronize()
+    th_h, lo_h = t2n(theta), t2n(local)
+    t0 = time.time()
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(th_h, lo_h, off)
+    say(f"[every element] oracle stage 1 on {N} elements: {time.time() - t0:.1f}s")
+    del lo_h
+    exact = check_qparams(B.qparams_to_numpy(qp1), o_qp)
+    flips = check_codes(t2n(codes1), o_codes, o_d, off, o_qp)
+    say(f"[every element] stage 1 codes compared ({time.time() - t_all:.0f}s)")
+    worst = check_luts(t2n(lut1), o_luts, o_codes, off, o_qp)
+    say(f"[every element] stage 1: {exact}/{T} ranges bit-equal, flips={flips}, worst lut rel={worst:.2e}")
+    del o_d, codes1, local
+    torch.cuda.empty_cache()
+
+    # stage 2: the oracle's stage-1 codes as contribution 0 (stage-isolated), three synthetic ones
+    peers = [torch.from_numpy(o_codes).to(DEV)]
+    luts = [torch.from_numpy(o_luts).to(DEV)]
+    for p in range(1, W):
+        peers.append(synth.fill_coded_contribution(torch.empty(N, dtype=torch.uint8, device=DEV), p))
+        luts.append(synth.synthetic_codebooks(T, p, device=DEV))
+    acc = torch.empty(N, dtype=torch.float32, device=DEV)
+    codes2 = torch.empty(N, dtype=torch.uint8, device=DEV)
+    _, lut2, qp2 = B.reduce_chunk(peers, luts, off, W, codes_out=codes2, workspace=ws)           # recompute form
+    _, lut2m, qp2m = B.reduce_chunk(peers, luts, off, W, acc_out=acc, codes_out=peers[W - 1],      # materialise form,
+                                    workspace=ws)                                                  # codes over a consumed input
+    torch.cuda.synchronize()
+    h_codes = [o_codes] + [None] * (W - 1)
+    # the host's copies of the synthetic contributions come from the generator again (the last one's device
+    # buffer now holds the materialise call's codes)
+    tmp = torch.empty(N, dtype=torch.uint8, device=DEV)
+    for p in range(1, W):
+        h_codes[p] = t2n(synth.fill_coded_contribution(tmp, p))
+    del tmp
+    say(f"[every element] stage 2 ran on the GPU, inputs on the host ({time.time() - t_all:.0f}s)")
+    t0 = time.time()
+    o_acc, o_c2, o_l2, o_q2 = oracle_mod.reduce(h_codes, [t2n(l) for l in luts], off, W)
+    say(f"[every element] oracle reduce: {time.time() - t0:.1f}s")
+    del h_codes, o_codes
+    for name, g_codes, g_lut, g_qp in (("recompute", codes2, lut2, qp2), ("materialise", peers[W - 1], lut2m, qp2m)):
+        exact = check_qparams(B.qparams_to_numpy(g_qp), o_q2)
+        flips = check_codes(t2n(g_codes), o_c2, o_acc, off, o_q2)
+        say(f"[every element] stage 2 ({name}) codes compared ({time.time() - t_all:.0f}s)")
+        worst = check_luts(t2n(g_lut), o_l2, o_c2, off, o_q2)
+        say(f"[every element] stage 2 ({name}): {exact}/{T} ranges bit-equal, flips={flips}, worst lut rel={worst:.2e}")
+    assert np.array_equal(t2n(acc), o_acc)              # the stored accumulation: a fixed sequence of fp32 operations
+    say(f"[every element] stored accumulation bit-equal ({time.time() - t_all:.0f}s)")
+    del o_acc, acc, peers
+    torch.cuda.empty_cache()
+
+    # stage 3 from the oracle's requantised result, two steps (the second with a non-zero momentum)
+    codes2.copy_(torch.from_numpy(o_c2))
+    lut2.copy_(torch.from_numpy(o_l2))
+    mom = torch.zeros(N, dtype=torch.float32, device=DEV)
+    m_h = np.zeros(N, dtype=np.float32)
+    # the oracle's new theta and momentum are copied up piece by piece and the comparison itself (the
+    # tolerance formula of parity_utils.check_outer) is evaluated on the device: 4 x 10^10 values
+    piece = 1 << 28
+    for step in range(2):
+        B.outer_step(theta, mom, LR, BETA, delta_codes=codes2, delta_lut=lut2, seg_offsets=off, workspace=ws)
+        oracle_mod.outer_step(th_h, m_h, LR, BETA, delta_codes=o_c2, delta_luts=o_l2, seg_offsets=off)
+        torch.cuda.synchronize()
+        worst = 0.0
+        for s in range(T):
+            for a in range(off[s], off[s + 1], piece):
+                b = min(a + piece, off[s + 1])
+                g = lut2[s][codes2[a:b].long()].abs().double()                  # the oracle's codes and codebook
+                m_o = torch.from_numpy(m_h[a:b]).to(DEV).double()
+                t_o = torch.from_numpy(th_h[a:b]).to(DEV).double()
+                for got, want, scale, what in ((mom[a:b], m_o, torch.maximum(m_o.abs(), g), "momentum"),
+                                               (theta[a:b], t_o, torch.maximum(t_o.abs(), LR * (g + BETA * m_o.abs())),
+                                                "theta")):
+                    rel = ((got.double() - want).abs() / scale.clamp_min(1e-300)).max()
+                    assert float(rel) <= 1e-5, f"{what}, step {step}, tensor {s}: {float(rel):.3e}"
+                    worst = max(worst, float(rel))
+        say(f"[every element] outer step {step + 1}: worst relative deviation {worst:.2e} ({time.time() - t_all:.0f}s)")
+    say(f"[every element] all three stages, {N} elements each: {time.time() - t_all:.0f}s")
 
 
 # ---------------------------------------------------------------------------------------------
