@@ -688,6 +688,39 @@ def test_config3_fullsize_sampled_tensors(B, oracle_mod):
     say("[config3] outer step checked on the sampled tensors")
 
 
+def test_config3_fullsize_stage1_every_element_heavy_tails(B, oracle_mod):
+    """Stage 1 on the full 10B buffer of Student-t (nu = 3) pseudo-gradients - values beyond 100 sigma occur -
+    every element and all 381 ranges against the oracle."""
+    import psutil
+    sizes = synth.config_segment_sizes(3)
+    off = synth.offsets_from_sizes(sizes)
+    N, T = off[-1], len(sizes)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 100e9:
+        pytest.skip(f"needs about 95 GB of free HBM, have {free / 1e9:.0f} GB")
+    if psutil.virtual_memory().available < 175e9:
+        pytest.skip(f"needs about 145 GB of host memory, {psutil.virtual_memory().available / 1e9:.0f} GB available")
+    t_all = time.time()
+    theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
+    local = synth.fill_theta_local(torch.empty(N, dtype=torch.float32, device=DEV), theta, 0, "student_t3")
+    codes, lut, qp = B.pseudograd_quantize(theta, local, off)
+    torch.cuda.synchronize()
+    th_h, lo_h = t2n(theta), t2n(local)
+    del theta, local
+    say(f"[config3 every element] inputs on the host ({time.time() - t_all:.0f}s)")
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(th_h, lo_h, off)
+    del th_h, lo_h
+    say(f"[config3 every element] oracle done ({time.time() - t_all:.0f}s); largest |d| / sigma = "
+        f"{float(np.abs(o_d[off[1]:off[2]]).max() / o_qp['std'][1]):.0f} in the first matrix")
+    exact = check_qparams(B.qparams_to_numpy(qp), o_qp)
+    flips = check_codes(t2n(codes), o_codes, o_d, off, o_qp)
+    say(f"[config3 every element] codes compared ({time.time() - t_all:.0f}s)")
+    worst = check_luts(t2n(lut), o_luts, o_codes, off, o_qp)
+    clipped = float(np.mean((o_codes[off[1]:off[2]] == 0) | (o_codes[off[1]:off[2]] == 255)))
+    say(f"[config3 every element] {exact}/{T} ranges bit-equal, flips={flips}, worst lut rel={worst:.2e}; "
+        f"{100 * clipped:.2f} % of the first matrix in the two end buckets ({time.time() - t_all:.0f}s)")
+
+
 # ---------------------------------------------------------------------------------------------
 # configuration 4 at full size: one whole ring chunk (729,384,375 elements, starting at an odd
 # element offset of the full-size buffers), 13 coded contributions + the fp32 local addend
