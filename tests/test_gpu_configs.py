@@ -688,13 +688,10 @@ def test_config3_fullsize_sampled_tensors(B, oracle_mod):
     say("[config3] outer step checked on the sampled tensors")
 
 
-def test_config3_fullsize_stage1_every_element_heavy_tails(B, oracle_mod):
-    """Stage 1 on the full 10B buffer of Student-t (nu = 3) pseudo-gradients - values beyond 100 sigma occur -
-    every element and all 381 ranges against the oracle."""
+def _stage1_every_element(B, oracle_mod, off, kind, local_dtype, label):
+    """Stage 1 on a full-size buffer, every element and every range against the oracle."""
     import psutil
-    sizes = synth.config_segment_sizes(3)
-    off = synth.offsets_from_sizes(sizes)
-    N, T = off[-1], len(sizes)
+    N, T = off[-1], len(off) - 1
     free, _ = torch.cuda.mem_get_info()
     if free < 100e9:
         pytest.skip(f"needs about 95 GB of free HBM, have {free / 1e9:.0f} GB")
@@ -702,23 +699,38 @@ def test_config3_fullsize_stage1_every_element_heavy_tails(B, oracle_mod):
         pytest.skip(f"needs about 145 GB of host memory, {psutil.virtual_memory().available / 1e9:.0f} GB available")
     t_all = time.time()
     theta = synth.fill_theta_outer(torch.empty(N, dtype=torch.float32, device=DEV))
-    local = synth.fill_theta_local(torch.empty(N, dtype=torch.float32, device=DEV), theta, 0, "student_t3")
+    local = synth.fill_theta_local(torch.empty(N, dtype=local_dtype, device=DEV), theta, 0, kind)
     codes, lut, qp = B.pseudograd_quantize(theta, local, off)
     torch.cuda.synchronize()
-    th_h, lo_h = t2n(theta), t2n(local)
+    bf16 = local_dtype == torch.bfloat16
+    th_h, lo_h = t2n(theta), (bf16_bits(local) if bf16 else t2n(local))
     del theta, local
-    say(f"[config3 every element] inputs on the host ({time.time() - t_all:.0f}s)")
-    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(th_h, lo_h, off)
+    say(f"[{label}] inputs on the host ({time.time() - t_all:.0f}s)")
+    o_codes, o_luts, o_qp, o_d = oracle_mod.pseudograd_quantize(th_h, lo_h, off, local_is_bf16=bf16)
     del th_h, lo_h
-    say(f"[config3 every element] oracle done ({time.time() - t_all:.0f}s); largest |d| / sigma = "
-        f"{float(np.abs(o_d[off[1]:off[2]]).max() / o_qp['std'][1]):.0f} in the first matrix")
-    exact = check_qparams(B.qparams_to_numpy(qp), o_qp)
+    a, b = off[min(1, T - 1)], off[min(1, T - 1) + 1]
+    say(f"[{label}] oracle done ({time.time() - t_all:.0f}s); largest |d| / sigma = "
+        f"{float(np.abs(o_d[a:b]).max() / o_qp['std'][min(1, T - 1)]):.0f} in group {min(1, T - 1)}")
+    exact = check_qparams(B.qparams_to_numpy(qp), o_qp, require_exact=1.0 if T < 100 else None)
     flips = check_codes(t2n(codes), o_codes, o_d, off, o_qp)
-    say(f"[config3 every element] codes compared ({time.time() - t_all:.0f}s)")
+    say(f"[{label}] codes compared ({time.time() - t_all:.0f}s)")
     worst = check_luts(t2n(lut), o_luts, o_codes, off, o_qp)
-    clipped = float(np.mean((o_codes[off[1]:off[2]] == 0) | (o_codes[off[1]:off[2]] == 255)))
-    say(f"[config3 every element] {exact}/{T} ranges bit-equal, flips={flips}, worst lut rel={worst:.2e}; "
-        f"{100 * clipped:.2f} % of the first matrix in the two end buckets ({time.time() - t_all:.0f}s)")
+    clipped = float(np.mean((o_codes[a:b] == 0) | (o_codes[a:b] == 255)))
+    say(f"[{label}] {exact}/{T} ranges bit-equal, flips={flips}, worst lut rel={worst:.2e}; "
+        f"{100 * clipped:.2f} % of group {min(1, T - 1)} in the two end buckets ({time.time() - t_all:.0f}s)")
+
+
+def test_config3_fullsize_stage1_every_element_heavy_tails(B, oracle_mod):
+    """Stage 1 on the full 10B buffer of Student-t (nu = 3) pseudo-gradients - values beyond 100 sigma occur."""
+    _stage1_every_element(B, oracle_mod, synth.offsets_from_sizes(synth.config_segment_sizes(3)), "student_t3",
+                          torch.float32, "config3 every element")
+
+
+def test_config4_fullsize_stage1_every_element_bf16_ring_chunks(B, oracle_mod):
+    """Stage 1 with a bf16 theta_local on the full 10B buffer cut into the 14 ring chunks (groups of 729,384,375
+    elements starting at odd offsets)."""
+    _stage1_every_element(B, oracle_mod, synth.offsets_from_sizes(synth.config_segment_sizes(4)), "mixture",
+                          torch.bfloat16, "config4 every element")
 
 
 # ---------------------------------------------------------------------------------------------
