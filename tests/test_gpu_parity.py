@@ -572,6 +572,40 @@ def test_large_mean_small_spread(B, oracle_mod):
     _check_stage1(B, oracle_mod, theta, local, off, "large mean")
 
 
+def test_values_on_bucket_edges(B, oracle_mod):
+    """A tensor with a few thousand values placed on the bucket edges themselves: lo + k / inv_w for every k, and
+    the fp32 neighbours just below and above.  The edges depend on the statistics of the tensor that holds
+    them, so the values are re-placed a few times until they stop moving.  On an edge the bucket is decided by
+    the rounding of two fp32 operations; both sides must take the same one, element by element."""
+    rng = np.random.default_rng(4)
+    n = 300_000
+    x = rng.normal(0.0, 1e-3, n).astype(np.float32)
+    slots = rng.choice(n, size=257 * 9, replace=False).reshape(257, 9)
+    for _ in range(8):
+        _, _, q = oracle_mod.quantize(x)
+        lo, w = np.float64(q["lo"]), 1.0 / np.float64(q["inv_w"])
+        for k in range(257):
+            e = np.float32(lo + k * w)
+            below, above = np.nextafter(e, np.float32(-1)), np.nextafter(e, np.float32(1))
+            x[slots[k]] = [e, below, above] * 3
+    o_codes, o_lut, o_q = oracle_mod.quantize(x)
+    t = ((x[slots.ravel()] - np.float32(o_q["lo"])) * np.float32(o_q["inv_w"])).astype(np.float64)
+    on_edge = np.abs(t - np.round(t)) < 1e-3
+    assert on_edge.mean() > 0.9, on_edge.mean()          # the placement converged: the values sit on the final edges
+    theta = torch.zeros(n, dtype=torch.float32, device=DEV)
+    local = torch.from_numpy(-x).to(DEV)                  # theta - local = x exactly
+    codes, luts, qp = B.pseudograd_quantize(theta, local, [0, n])
+    torch.cuda.synchronize()
+    g_q = B.qparams_to_numpy(qp)
+    check_qparams(g_q, np.array([o_q]), require_exact=1.0)
+    assert np.array_equal(t2n(codes), o_codes)            # not one flip, on the edges or anywhere else
+    check_luts(t2n(luts), o_lut.reshape(1, 256), o_codes, [0, n], np.array([o_q]))
+    both_sides = len(set(o_codes[slots[100]].tolist()))
+    say(f"[edges] {int(on_edge.sum())} of {on_edge.size} planted values within 1e-3 of an edge; "
+        f"the nine values around edge 100 fall into {both_sides} buckets")
+    assert both_sides == 2
+
+
 def test_few_distinct_values_reconstruct(B, oracle_mod):
     """A tensor with 16 well separated levels: every bucket holds one distinct value.  The oracle
     decodes it bit-exactly; the library's fixed-point bucket sums round each offset to 2^-22 of a
